@@ -1,0 +1,348 @@
+"""Pins of the CPU oracle to things other than itself (no GPU needed).
+
+Each test names what it fixes.  Citations are to the paper's sections / equations.
+"""
+import math
+
+import pytest
+import torch
+
+from oracle import firp_oracle as fo
+from paper_2410_20488_amd import synth
+from tests.helpers import MICRO, make_oracle
+
+F64 = torch.float64
+
+
+def _micro(dtype=F64, with_bias=True, cfg=MICRO, **kw):
+    w = synth.make_weights(cfg, "cpu", with_bias=with_bias, std=0.08)
+    return make_oracle(cfg, w, dtype=dtype, **kw), w
+
+
+# ------------------------------------------------------------------ library-routine pins
+
+
+def test_rms_norm_matches_library_routine():
+    g = torch.Generator().manual_seed(1)
+    x = torch.randn(5, 48, generator=g, dtype=F64)
+    gain = torch.randn(48, generator=g, dtype=F64)
+    ref = torch.nn.functional.rms_norm(x, (48,), gain, eps=1e-5)
+    assert torch.allclose(fo.rms_norm(x, gain, 1e-5), ref, atol=1e-13)
+
+
+def test_masked_attention_matches_library_routine_with_grouped_heads():
+    g = torch.Generator().manual_seed(2)
+    T, S, Hq, Hkv, dh = 5, 11, 6, 2, 8
+    q = torch.randn(T, Hq, dh, generator=g, dtype=F64)
+    K = torch.randn(S, Hkv, dh, generator=g, dtype=F64)
+    V = torch.randn(S, Hkv, dh, generator=g, dtype=F64)
+    vis = torch.rand(T, S, generator=g) < 0.5
+    vis[:, 0] = True
+    ref = torch.nn.functional.scaled_dot_product_attention(
+        q.permute(1, 0, 2)[None], K.permute(1, 0, 2)[None], V.permute(1, 0, 2)[None],
+        attn_mask=vis[None, None], enable_gqa=True)[0].permute(1, 0, 2)
+    assert torch.allclose(fo.masked_attention(q, K, V, vis), ref, atol=1e-12)
+
+
+def test_masked_attention_single_visible_key_returns_its_value():
+    # closed form: softmax over one key is 1
+    q = torch.randn(2, 2, 4, dtype=F64)
+    K = torch.randn(3, 1, 4, dtype=F64)
+    V = torch.randn(3, 1, 4, dtype=F64)
+    vis = torch.tensor([[False, True, False], [False, False, True]])
+    out = fo.masked_attention(q, K, V, vis)
+    assert torch.allclose(out[0, 0], V[1, 0]) and torch.allclose(out[1, 1], V[2, 0])
+
+
+def test_rope_closed_forms():
+    # dh = 2: a single pair rotating by exactly `pos` radians (frequency base^0 = 1)
+    x = torch.tensor([[[1.0, 0.0]]], dtype=F64)
+    for p in (0, 1, 7):
+        y = fo.rope_rotate(x, torch.tensor([p]), 10000.0)
+        assert torch.allclose(y[0, 0], torch.tensor([math.cos(p), math.sin(p)], dtype=F64), atol=1e-14)
+    # dh = 4: pairs are (0,2) and (1,3); the second pair turns at base^(-1/2)
+    x = torch.tensor([[[0.0, 1.0, 0.0, 0.0]]], dtype=F64)
+    y = fo.rope_rotate(x, torch.tensor([3]), 100.0)
+    a = 3 * 100.0 ** -0.5
+    assert torch.allclose(y[0, 0], torch.tensor([0.0, math.cos(a), 0.0, math.sin(a)], dtype=F64), atol=1e-14)
+
+
+def test_rope_relative_position_property_and_norm():
+    g = torch.Generator().manual_seed(3)
+    q = torch.randn(1, 1, 16, generator=g, dtype=F64)
+    k = torch.randn(1, 1, 16, generator=g, dtype=F64)
+
+    def dot(m, n):
+        return float((fo.rope_rotate(q, torch.tensor([m]), 10000.0)
+                      * fo.rope_rotate(k, torch.tensor([n]), 10000.0)).sum())
+    assert abs(dot(5, 2) - dot(13, 10)) < 1e-12          # depends on m - n only
+    assert abs(dot(5, 2) - dot(2, 5)) > 1e-6             # ... and on its sign
+    assert torch.allclose(fo.rope_rotate(q, torch.tensor([0]), 10000.0), q)
+    assert abs(float(fo.rope_rotate(q, torch.tensor([9]), 10000.0).norm() - q.norm())) < 1e-12
+
+
+def test_decoder_matches_huggingface_llama():
+    """The paper's implementation is HuggingFace's LLaMA; the oracle's plain causal forward
+    must give the same logits for the same weights (pins RMSNorm placement, rotary pairing,
+    grouped heads, SwiGLU, [out,in] weight orientation, untied lm-head)."""
+    transformers = pytest.importorskip("transformers")
+    cfg = MICRO
+    o, w = _micro(dtype=torch.float64, with_bias=False)
+    hf_cfg = transformers.LlamaConfig(
+        vocab_size=cfg.vocab, hidden_size=cfg.d_model, intermediate_size=cfg.d_ffn,
+        num_hidden_layers=cfg.n_layers, num_attention_heads=cfg.n_q_heads,
+        num_key_value_heads=cfg.n_kv_heads, head_dim=cfg.head_dim, rms_norm_eps=cfg.rms_eps,
+        rope_theta=cfg.rope_base, max_position_embeddings=256, tie_word_embeddings=False,
+        attention_bias=False, mlp_bias=False, hidden_act="silu", attn_implementation="eager")
+    model = transformers.LlamaForCausalLM(hf_cfg).double().eval()
+    sd = {"model.embed_tokens.weight": w["embed"], "lm_head.weight": w["lm_head"],
+          "model.norm.weight": w["norm_final"]}
+    hf_names = {"wq": "self_attn.q_proj", "wk": "self_attn.k_proj", "wv": "self_attn.v_proj",
+                "wo": "self_attn.o_proj", "w_gate": "mlp.gate_proj", "w_up": "mlp.up_proj",
+                "w_down": "mlp.down_proj", "norm_attn": "input_layernorm",
+                "norm_mlp": "post_attention_layernorm"}
+    for i in range(cfg.n_layers):
+        for ours, theirs in hf_names.items():
+            sd[f"model.layers.{i}.{theirs}.weight"] = w[ours][i]
+    missing = model.load_state_dict({k: v.double() for k, v in sd.items()}, strict=False)
+    assert not [m for m in missing.missing_keys if "rotary" not in m]
+    toks = synth.prompt_tokens(5, 19, cfg.vocab)
+    with torch.no_grad():
+        ref = model(input_ids=toks.long()[None]).logits[0]
+    got = o.causal_forward(toks.tolist())
+    # HF builds its rotary cos/sin tables in fp32 even for a double model: agreement is to ~1e-7
+    assert (got - ref).abs().max() < 2e-6 and float(ref.std()) > 0.1
+
+
+# ------------------------------------------------------------------ step-level pins
+
+
+def _tree_args(t: synth.Tree):
+    return dict(parent=list(t.parent), rank=list(t.rank), anchor=list(t.anchor))
+
+
+def _random_candidates(seed, n, vocab):
+    return synth.prompt_tokens(seed, n, vocab, stream=9).tolist()
+
+
+def test_k0_root_only_steps_equal_cache_free_greedy():
+    """Eq. 1 with no drafts: the step machinery (cache, commit, positions) is ordinary greedy."""
+    import dataclasses
+    cfg = dataclasses.replace(MICRO, k=0)
+    o, _ = _micro(cfg=cfg)
+    prompt = synth.prompt_tokens(11, 9, cfg.vocab).tolist()
+    want = o.greedy(prompt, 8)
+    got = [o.prefill(prompt)]
+    chain = synth.chain_tree(3, "none")
+    while len(got) < 8:
+        r = o.step(**_tree_args(chain))
+        assert len(r.tokens) == 1 and r.ran_root_only
+        got += r.tokens
+    assert got == want
+
+
+@pytest.mark.parametrize("anchors", ["root", "all"])
+def test_tree_rows_equal_brute_force_per_path(anchors):
+    """Tree attention: every node's logits equal a plain causal pass over prompt + its path;
+    every pseudo row equals a plain causal chain with the mapped rows inserted at the FIRP
+    layer (positions +1..+k, each seeing the earlier ones)."""
+    o, w = _micro()
+    cfg = MICRO
+    prompt = synth.prompt_tokens(21, 7, cfg.vocab).tolist()
+    o.prefill(prompt)
+    tree = synth.random_tree(5, 9, 3, 3, 0.5) if anchors == "root" else synth.full_tree((2, 2), "all")
+    if anchors == "root":
+        tree = synth.Tree(tree.parent, tree.rank, (1,) + tree.anchor[1:])
+    cand = _random_candidates(3, tree.n_nodes, cfg.vocab)
+    committed = prompt + [o.root_token]
+    res = o.step(**_tree_args(tree), node_tokens=cand)
+    toks = res.node_tokens
+    brute = make_oracle(cfg, w, dtype=F64)
+    for v in range(tree.n_nodes):
+        path = fo.tree_ancestors(tree.parent, v) + [v]
+        seq = committed[:-1] + [toks[u] for u in path]
+        ref = brute.causal_forward(seq)[-1]
+        assert (res.logits[v] - ref).abs().max() < 1e-9, f"node {v}"
+        if tree.anchor[v]:
+            n = len(seq)
+            x = brute._embed(seq)
+            empty = torch.zeros(0, cfg.n_kv_heads, cfg.head_dim, dtype=F64)
+            for layer in range(cfg.firp_layer):
+                x, _, _ = brute._layer(layer, x, torch.arange(n), empty, empty,
+                                       torch.tril(torch.ones(n, n, dtype=torch.bool)))
+            extra = [w["proj_w"][i].double() @ x[-1] + w["proj_b"][i].double() for i in range(cfg.k)]
+            x = torch.cat([x, torch.stack(extra)])
+            m = n + cfg.k
+            for layer in range(cfg.firp_layer, cfg.n_layers):
+                x, _, _ = brute._layer(layer, x, torch.arange(m), empty, empty,
+                                       torch.tril(torch.ones(m, m, dtype=torch.bool)))
+            ref_p = brute._logits(x)[n:]
+            first = tree.n_nodes + [a for a, _ in res.rows.pseudo_of].index(v)
+            assert (res.logits[first:first + cfg.k] - ref_p).abs().max() < 1e-9, f"pseudo of {v}"
+
+
+@pytest.mark.parametrize("anchors,seed", [("root", 1), ("all", 2), ("none", 3)])
+def test_losslessness_against_cache_free_greedy(anchors, seed):
+    """Whatever the tree, anchors and (untrained) maps, the concatenated step outputs are the
+    sequential greedy continuation (Eq. 1, 'lossless')."""
+    o, _ = _micro()
+    cfg = MICRO
+    prompt = synth.prompt_tokens(30 + seed, 6, cfg.vocab).tolist()
+    m = 14
+    want = o.greedy(prompt, m)
+    got = [o.prefill(prompt)]
+    tree = synth.with_anchors(synth.full_tree((3, 2)), anchors)
+    step = 0
+    while len(got) < m:
+        step += 1
+        if step % 3 == 0:      # inject candidates that contain part of the true continuation
+            cand = _random_candidates(step, tree.n_nodes, cfg.vocab)
+            nxt = want[len(got):len(got) + 2]
+            for v in (1, 3):                                    # keep the other siblings wrong
+                cand[v] = (nxt[0] + v) % cfg.vocab
+            cand[2] = nxt[0]                                   # a non-first child of the root
+            kids = [v for v in range(tree.n_nodes) if tree.parent[v] == 2]
+            if len(nxt) > 1:
+                cand[kids[0]] = (nxt[1] + 1) % cfg.vocab
+                cand[kids[-1]] = nxt[1]
+            r = o.step(**_tree_args(tree), node_tokens=cand)
+            assert len(r.tokens) == min(3, len(nxt) + 1) and r.path[:2] == [0, 2]
+        else:
+            r = o.step(**_tree_args(tree))
+        assert 1 <= len(r.tokens) <= cfg.k + 1
+        got += r.tokens
+    assert got[:m] == want
+
+
+def test_forced_acceptance_lengths_and_sibling_choice():
+    o, w = _micro()
+    cfg = MICRO
+    prompt = synth.prompt_tokens(41, 8, cfg.vocab).tolist()
+    g = o.greedy(prompt, 6)
+    chain = synth.chain_tree(3, "root")
+    for corrupt_depth in (None, 1, 2, 3):
+        o.prefill(prompt)                                   # root token = g[0]
+        cand = [0, g[1], g[2], g[3]]
+        if corrupt_depth is not None:
+            cand[corrupt_depth] = (cand[corrupt_depth] + 1) % cfg.vocab
+        r = o.step(**_tree_args(chain), node_tokens=cand)
+        a = 3 if corrupt_depth is None else corrupt_depth - 1
+        assert r.tokens == g[1:a + 2] and r.path == list(range(a + 1))
+        assert o.p0 == len(prompt) + a + 1 and o.root_token == g[a + 1]
+    # the right token on the last sibling: the path goes through it; duplicates -> lowest node
+    o.prefill(prompt)
+    tree = synth.full_tree((3, 1), "none")                  # nodes 1,2,3 children of root; 4,5,6 below
+    cand = [0, g[1] + 1, g[1], g[1], 7, g[2], g[2]]
+    r = o.step(**_tree_args(tree), node_tokens=[c % cfg.vocab for c in cand])
+    assert r.path == [0, 2, 5] and r.tokens == g[1:4]
+    assert r.drafts is None                                 # path ended at a non-anchor
+    r2 = o.step(**_tree_args(tree))                         # no drafts -> root-only
+    assert r2.ran_root_only and r2.tokens == [g[4]]
+
+
+def test_commit_equals_prefill_and_kv_rounding_is_storage_only():
+    for kv_round in (False, True):
+        o, w = _micro(kv_round=kv_round)
+        cfg = MICRO
+        prompt = synth.prompt_tokens(51, 5, cfg.vocab).tolist()
+        out = [o.prefill(prompt)]
+        tree = synth.full_tree((2, 2), "all")
+        for s in range(4):
+            g_next = o.greedy(prompt + out, 2) if not kv_round else None
+            cand = _random_candidates(s, tree.n_nodes, cfg.vocab)
+            if g_next is not None:
+                cand[1] = g_next[0]
+            out += o.step(**_tree_args(tree), node_tokens=cand).tokens
+        ref = make_oracle(cfg, w, dtype=F64, kv_round=kv_round)
+        committed = (prompt + out)[:o.p0]
+        ref.causal_forward(committed, keep_cache=True)
+        assert o.p0 == len(prompt) + len(out) - 1
+        for layer in range(cfg.n_layers):
+            assert (o.K[layer] - ref.K[layer]).abs().max() < 1e-10
+            assert (o.V[layer] - ref.V[layer]).abs().max() < 1e-10
+            if kv_round:
+                assert torch.equal(o.K[layer], fo.round_to_bf16(o.K[layer]))
+
+
+def test_real_rows_do_not_depend_on_pseudo_rows_or_non_ancestors():
+    o, w = _micro()
+    cfg = MICRO
+    prompt = synth.prompt_tokens(61, 6, cfg.vocab).tolist()
+    tree = synth.full_tree((2, 2), "all")
+    cand = _random_candidates(1, tree.n_nodes, cfg.vocab)
+    o.prefill(prompt)
+    base = o.step(**_tree_args(tree), node_tokens=cand).logits
+    # other anchors, other maps
+    w2 = dict(w)
+    w2["proj_w"] = [p * 3.0 for p in w["proj_w"]]
+    o2 = make_oracle(cfg, w2, dtype=F64)
+    o2.prefill(prompt)
+    alt = o2.step(**_tree_args(synth.with_anchors(tree, "root")), node_tokens=cand).logits
+    assert torch.equal(base[:tree.n_nodes], alt[:tree.n_nodes])
+    assert not torch.equal(base[tree.n_nodes:tree.n_nodes + cfg.k], alt[tree.n_nodes:])
+    # a node outside the ancestor set of node 3 (= child of node 1): change node 2's token
+    cand2 = list(cand)
+    cand2[2] = (cand2[2] + 1) % cfg.vocab
+    o.prefill(prompt)
+    alt2 = o.step(**_tree_args(tree), node_tokens=cand2).logits
+    assert tree.parent[3] == 1
+    assert torch.equal(base[3], alt2[3]) and not torch.equal(base[2], alt2[2])
+
+
+def test_position_ids_of_tree_and_pseudo_rows():
+    rows = fo.build_rows([-1, 0, 0, 1, 3], [1, 0, 0, 1, 0], 2)
+    assert rows.pos_off == [0, 1, 1, 2, 3, 1, 2, 3, 4]       # siblings share a position id
+    assert rows.pseudo_of == [(0, 1), (0, 2), (3, 1), (3, 2)]
+    assert rows.sees[4] == [0, 1, 3, 4]
+    assert rows.sees[6] == [0, 5, 6]                         # second pseudo row sees the first
+    assert rows.sees[7] == [0, 1, 3, 7] and rows.sees[8] == [0, 1, 3, 7, 8]
+
+
+def test_ties_go_to_the_lower_token_id():
+    cfg = MICRO
+    w = synth.make_weights(cfg, "cpu", with_bias=True, std=0.08)
+    o = make_oracle(cfg, w, dtype=F64, b_max=4)
+    prompt = synth.prompt_tokens(71, 6, cfg.vocab).tolist()
+    first = o.prefill(prompt)
+    top = o.drafts[1]                       # second pseudo row's candidates
+
+    def with_twin(src, twin):
+        """lm-head with row `twin` an exact copy of row `src`: the two logits tie everywhere."""
+        lm = w["lm_head"].clone()
+        lm[twin] = lm[src]
+        w2 = dict(w)
+        w2["lm_head"] = lm
+        o2 = make_oracle(cfg, w2, dtype=F64, b_max=4)
+        return o2.prefill(prompt), o2.drafts[1]
+
+    hi = next(t for t in range(first + 1, cfg.vocab) if t not in top)
+    assert with_twin(first, hi)[0] == first
+    if first > 0:
+        assert with_twin(first, first - 1)[0] == first - 1
+    src = top[0]
+    hi = next(t for t in range(src + 1, cfg.vocab) if t != first)
+    assert with_twin(src, hi)[1][:2] == [src, hi]
+    if src > 0 and src - 1 != first:
+        assert with_twin(src, src - 1)[1][:2] == [src - 1, src]
+
+
+def test_draft_size_closed_form():
+    # Table 1: draft sizes 0.08 B (13B) and 0.05 B (7B) are k = 3 full d x d maps
+    assert round(3 * 5120 ** 2 / 1e9, 2) == 0.08 and round(3 * 4096 ** 2 / 1e9, 2) == 0.05
+    w = synth.make_weights(MICRO, "cpu")
+    assert len(w["proj_w"]) == MICRO.k and w["proj_w"][0].shape == (MICRO.d_model, MICRO.d_model)
+
+
+def test_config1_fp32_32_steps_lossless():
+    """The small benchmark configuration end to end, in the oracle's default fp32."""
+    cfg = synth.CONFIGS["tiny"]
+    w = synth.make_weights(cfg, "cpu")
+    o = make_oracle(cfg, w)
+    prompt = synth.prompt_tokens(cfg.seed, 64, cfg.vocab).tolist()
+    tree = synth.workload_tree("tiny")
+    got = [o.prefill(prompt)]
+    for _ in range(32):
+        got += o.step(**_tree_args(tree)).tokens
+    o64 = make_oracle(cfg, w, dtype=F64)
+    want = o64.greedy(prompt, 12)
+    assert got[:12] == want
