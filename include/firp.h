@@ -1,0 +1,189 @@
+/*
+ * firp.h - C ABI of the MI355X-native FIRP decoding step.
+ *
+ * FIRP (Methodology / FIRP; Inference stage; Tree attention): in one forward pass of a
+ * LLaMA-style decoder, k linear maps W_i h + b_i (Eq. 3) placed at an intermediate layer turn
+ * the hidden state of a real token into k pseudo hidden states for the next k positions.  The
+ * pseudo states, the real token and a tree of draft candidates run through the remaining
+ * layers under a tree attention mask over the KV cache; the original lm-head verifies the
+ * candidates greedily (longest accepted path) and drafts the next tree from the pseudo rows;
+ * the accepted path is committed to the cache.  The returned tokens are exactly those of
+ * sequential greedy decoding (Eq. 1).
+ *
+ * Conventions
+ *  - Every call returns FIRP_OK or a negative firp_status; firp_last_error() gives text.
+ *  - All argument and capacity checks run on the host before anything is enqueued; a failed
+ *    call leaves the context unchanged.
+ *  - The library never allocates or frees device memory and creates no streams: weights, the
+ *    workspace and the stream are the caller's.  Pointers marked DEVICE must be device
+ *    addresses valid on the current HIP device; pointers marked HOST are ordinary host memory
+ *    read or written during the call only.
+ *  - Weights are `[out, in]` row-major in `dtype`, borrowed: they must outlive the context
+ *    and are never written.
+ *  - One context, one thread.  Calls on one context are serialised by the caller.
+ */
+#ifndef FIRP_H
+#define FIRP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct firp_ctx firp_ctx;
+
+typedef enum {
+  FIRP_OK = 0,
+  FIRP_EINVAL = -1,    /* malformed argument (null, out of range, bad tree, bad dtype) */
+  FIRP_ESTATE = -2,    /* call out of order (step before prefill) */
+  FIRP_ECAPACITY = -3, /* exceeds max_ctx / max_nodes / max_rows / workspace */
+  FIRP_EDEVICE = -4    /* a HIP call failed */
+} firp_status;
+
+typedef enum { FIRP_F32 = 0, FIRP_BF16 = 1 } firp_dtype;
+
+#define FIRP_MAX_K 8      /* pseudo hidden states per anchor */
+#define FIRP_MAX_B 16     /* candidates kept per future position (top-b) */
+#define FIRP_MAX_ROWS 256 /* rows of one sequence in one step: N + k*|A| */
+
+/* Shapes, numerics and capacities (the decoder of Experiment / Setup: LLaMA-2 style). */
+typedef struct {
+  int32_t n_layers, d_model, n_q_heads, n_kv_heads, head_dim, d_ffn, vocab;
+  float rms_eps, rope_base;
+  int32_t dtype;     /* firp_dtype of weights and KV cache */
+  int32_t max_ctx;   /* committed tokens the cache can hold, per sequence */
+  int32_t max_batch; /* independent sequences */
+  int32_t max_nodes; /* N, tree nodes including the root */
+  int32_t max_rows;  /* N + k*|A| <= FIRP_MAX_ROWS; also the prefill chunk length */
+  int32_t b_max;     /* top-b kept per pseudo row, 1..FIRP_MAX_B */
+} firp_model_desc;
+
+/* DEVICE pointers.  Per-layer entries are HOST arrays of n_layers DEVICE pointers. */
+typedef struct {
+  const void *embed;             /* [V, d] */
+  const void *const *wq;         /* [Hq*dh, d] */
+  const void *const *wk;         /* [Hkv*dh, d] */
+  const void *const *wv;         /* [Hkv*dh, d] */
+  const void *const *wo;         /* [d, Hq*dh] */
+  const void *const *w_gate;     /* [F, d] */
+  const void *const *w_up;       /* [F, d] */
+  const void *const *w_down;     /* [d, F] */
+  const void *const *norm_attn;  /* [d] */
+  const void *const *norm_mlp;   /* [d] */
+  const void *norm_final;        /* [d] */
+  const void *lm_head;           /* [V, d] */
+} firp_weights;
+
+/*
+ * Draft-tree topology (Tree attention: "a pre-defined tree structure and parser").
+ * HOST arrays borrowed for the call.  Node 0 is the root: the last emitted token, which is
+ * not yet in the cache.  Nodes are in topological order.  Node v at depth j >= 1 carries the
+ * candidate drafts[j-1][rank[v]] produced by the previous step.  anchor[v] = 1 gives node v
+ * k pseudo rows (Eq. 3 applied to its hidden state); the next tree can be drafted only if the
+ * accepted path ends at an anchor, otherwise the next step runs on the root alone.
+ */
+typedef struct {
+  int32_t n_nodes;        /* N >= 1 */
+  const int32_t *parent;  /* parent[0] = -1, 0 <= parent[v] < v */
+  const int32_t *rank;    /* 0 <= rank[v] < b_max; ignored for the root */
+  const uint8_t *anchor;  /* NULL = every node is an anchor */
+} firp_tree;
+
+/* Bytes of DEVICE workspace firp_init needs for this description (0 on invalid input). */
+size_t firp_workspace_bytes(const firp_model_desc *desc, int32_t k);
+
+/*
+ * Create a context (FIRP: k maps at one intermediate layer).
+ *  proj_w: HOST array of k DEVICE pointers, each [d, d]; proj_b: same for [d], or NULL.
+ *  layer_l: the pseudo rows enter decoder layer `layer_l` (0-based): they are computed from
+ *           the residual stream after layer_l layers and traverse n_layers - layer_l layers.
+ *  workspace: DEVICE, >= firp_workspace_bytes, 256-byte aligned, owned by the caller and
+ *           used exclusively by this context until firp_destroy.
+ *  hip_stream: hipStream_t on which all work is enqueued (0 = the null stream).
+ */
+firp_status firp_init(firp_ctx **out, const firp_model_desc *desc, const firp_weights *weights,
+                      const void *const *proj_w, const void *const *proj_b, int32_t layer_l,
+                      int32_t k, void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * Start `batch` sequences (Inference stage, first round): run the prompt through the decoder
+ * to fill the cache, then a root-only step on the last prompt token.
+ *  tokens: HOST, the prompts concatenated; lens: HOST [batch], each >= 1 and <= max_ctx.
+ *  first_token: HOST [batch], receives the first generated token of each sequence.
+ * Synchronises the stream before returning.
+ */
+firp_status firp_prefill(firp_ctx *ctx, int32_t batch, const int32_t *tokens,
+                         const int32_t *lens, int32_t *first_token);
+
+/*
+ * One decoding step (Inference stage): verify the tree drafted by the previous step, emit
+ * the accepted candidates plus one more token, draft the next tree, commit the path.
+ *  accepted: HOST [batch][FIRP_MAX_K + 1]; row b receives n_accepted[b] tokens in order
+ *            (the accepted candidates, then the token that follows them).
+ *  n_accepted: HOST [batch], each in 1 .. (deepest level of `tree`) + 1.
+ * The tree may be at most FIRP_MAX_K levels deep; levels beyond k receive no candidates from
+ * the drafts (they can only be filled through firp_step_with_candidates).
+ * Synchronises the stream before returning (the step's only synchronisation).
+ */
+firp_status firp_step(firp_ctx *ctx, const firp_tree *tree, int32_t *accepted,
+                      int32_t *n_accepted);
+
+/* Drop all sequences (the cache becomes empty); weights and workspace stay. */
+firp_status firp_reset(firp_ctx *ctx);
+
+/* Free host state.  The workspace and the weights remain the caller's. */
+void firp_destroy(firp_ctx *ctx);
+
+/* Text of the last error on this context (or of the last failed firp_init when ctx is NULL). */
+const char *firp_last_error(const firp_ctx *ctx);
+
+/* ---- test / debug surface (not on the hot path) ------------------------------------- */
+
+/* As firp_step, but the candidates come from the caller: node_tokens HOST [batch][N],
+ * entry 0 of each row ignored (the root is always the last emitted token). */
+firp_status firp_step_with_candidates(firp_ctx *ctx, const firp_tree *tree,
+                                      const int32_t *node_tokens, int32_t *accepted,
+                                      int32_t *n_accepted);
+
+/* Run only the host-side validation of a topology against this context's capacities (what
+ * firp_step does first); n_rows (may be NULL) receives N + k*|A|.  Touches no device. */
+firp_status firp_check_tree(firp_ctx *ctx, const firp_tree *tree, int32_t *n_rows);
+
+/* Logits of the last step, HOST [batch][T_hi][V] fp32, rows in step order (tree nodes, then
+ * for each anchor in ascending node id its k pseudo rows).  n_rows receives T_hi. */
+firp_status firp_debug_last_logits(firp_ctx *ctx, float *logits, int32_t *n_rows);
+
+/* Node ids of the last accepted path, HOST [batch][FIRP_MAX_K + 1]. */
+firp_status firp_debug_last_path(firp_ctx *ctx, int32_t *path_nodes);
+
+/* Current drafts, HOST [batch][k][b_max]; valid HOST [batch] (0 = next step is root-only). */
+firp_status firp_get_drafts(const firp_ctx *ctx, int32_t *drafts, int32_t *valid);
+
+/* Committed cache length of each sequence, HOST [batch]. */
+firp_status firp_get_ctx_len(const firp_ctx *ctx, int32_t *len);
+
+/* Copy the committed cache of one layer to the host as fp32: k_out, v_out HOST
+ * [len][Hkv][dh] (len = committed length of sequence `seq`). */
+firp_status firp_debug_read_cache(firp_ctx *ctx, int32_t seq, int32_t layer, float *k_out,
+                                  float *v_out);
+
+/* Behaviour switches for tests and measurements.  name = "gemm" value 0 (plain tiled kernel)
+ * or 1 (MFMA weight-streaming kernel, bf16 models only); "graph" 0/1 (replay the step from
+ * a captured HIP graph).  Returns FIRP_EINVAL for an unknown name or value. */
+firp_status firp_set_option(firp_ctx *ctx, const char *name, int32_t value);
+
+/* Standalone entry to the projection kernel for per-kernel parity and bandwidth tests:
+ * y[R, n] (DEVICE fp32) = x[R, K] (DEVICE fp32) . w[n, K]^T (DEVICE, `dtype`), on `hip_stream`,
+ * using `workspace` (DEVICE, >= firp_gemm_workspace_bytes(R, n, K)) for operand planes and
+ * split-K partial sums.  `kind` selects the kernel as the "gemm" option does. */
+size_t firp_gemm_workspace_bytes(int32_t rows, int32_t n, int32_t k_dim);
+firp_status firp_debug_gemm(const float *x, const void *w, float *y, int32_t rows, int32_t n,
+                            int32_t k_dim, int32_t dtype, int32_t kind, void *workspace,
+                            size_t workspace_bytes, void *hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FIRP_H */

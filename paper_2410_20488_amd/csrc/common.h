@@ -1,0 +1,106 @@
+// Shared device/host helpers of the FIRP step library (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace firp {
+
+// ---- element types -----------------------------------------------------------------------
+struct bf16 {
+  unsigned short v;
+};
+
+__device__ __forceinline__ float to_f32(float x) { return x; }
+__device__ __forceinline__ float to_f32(bf16 x) { return __uint_as_float(((unsigned)x.v) << 16); }
+
+// round-to-nearest-even fp32 -> bf16 (NaN stays NaN)
+__device__ __forceinline__ bf16 f32_to_bf16(float f) {
+  unsigned u = __float_as_uint(f);
+  bf16 r;
+  if ((u & 0x7fffffffu) > 0x7f800000u) {
+    r.v = (unsigned short)((u >> 16) | 0x40);
+  } else {
+    u += 0x7fffu + ((u >> 16) & 1u);
+    r.v = (unsigned short)(u >> 16);
+  }
+  return r;
+}
+
+template <typename T>
+__device__ __forceinline__ void store_elt(T* p, float v);
+template <>
+__device__ __forceinline__ void store_elt<float>(float* p, float v) { *p = v; }
+template <>
+__device__ __forceinline__ void store_elt<bf16>(bf16* p, float v) { *p = f32_to_bf16(v); }
+
+// ---- activations handed to a projection -----------------------------------------------------
+// fp32 models keep activations in fp32.  bf16 models hand the MFMA kernel two bf16 planes,
+// hi = rne(v) and lo = rne(v - hi): together they carry ~16 mantissa bits, so rounding the
+// activations costs no accuracy while both MFMA operands stay bf16.
+struct Act {
+  float* f32;  // [rows][ld] or nullptr
+  bf16* hi;    // [rows][ld] or nullptr
+  bf16* lo;
+  int ld;
+};
+
+template <bool SPLIT>
+__device__ __forceinline__ void act_store(const Act& a, size_t idx, float v) {
+  if constexpr (SPLIT) {
+    bf16 h = f32_to_bf16(v);
+    a.hi[idx] = h;
+    a.lo[idx] = f32_to_bf16(v - to_f32(h));
+  } else {
+    a.f32[idx] = v;
+  }
+}
+
+// ---- split-K partial sums ------------------------------------------------------------------
+// A projection leaves S partial products [S][rows][n] (fp32); its consumer adds them up.
+struct Partial {
+  const float* p;
+  int S;
+  size_t stride;  // elements between consecutive splits
+  int ld;         // n
+};
+
+__device__ __forceinline__ float partial_sum(const Partial& q, size_t idx) {
+  float v = q.p[idx];
+  for (int s = 1; s < q.S; ++s) v += q.p[idx + (size_t)s * q.stride];
+  return v;
+}
+
+// ---- per-row tables of one step (device) ---------------------------------------------------
+// Rows of a step: the tree nodes of every sequence first (sequence-major), then the pseudo rows.
+// `local` is the row's index inside its own sequence (node id, or N + pseudo index): its K/V
+// live at cache slot p0[seq] + local and bit `local` of another row's mask says "visible".
+#define FIRP_MASK_WORDS 4
+struct RowTab {
+  const int* seq;
+  const int* local;
+  const int* pos_off;                // position id = p0[seq] + pos_off
+  const unsigned long long* mask;    // [rows][FIRP_MASK_WORDS]
+};
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+  return v;
+}
+
+// block-wide sum for blockDim.x == 256 (4 waves)
+__device__ __forceinline__ float block_sum_256(float v, float* smem4) {
+  v = wave_sum(v);
+  int w = threadIdx.x >> 6;
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) smem4[w] = v;
+  __syncthreads();
+  return smem4[0] + smem4[1] + smem4[2] + smem4[3];
+}
+
+}  // namespace firp

@@ -1,0 +1,785 @@
+// Step engine and C ABI: validates, parses the tree (host), sequences the kernels of
+// firp_prefill / firp_step on the caller's stream, owns the carve-up of the workspace.
+#include <algorithm>
+#include <cstdarg>
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+#include <string>
+#include <vector>
+
+#include "../../include/firp.h"
+#include "kernels.h"
+
+using namespace firp;
+
+namespace {
+
+std::string g_init_error;
+
+inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+struct Carver {
+  char* base;
+  size_t off = 0;
+  template <typename T>
+  T* take(size_t count) {
+    off = align_up(off, 256);
+    T* p = base ? reinterpret_cast<T*>(base + off) : nullptr;
+    off += count * sizeof(T);
+    return p;
+  }
+};
+
+struct HostTree {
+  int B = 0, N = 0, P = 0, k = 0, n_anchor = 0, max_depth = 0;
+  std::vector<int> parent, rank, depth;
+  std::vector<uint8_t> anchor;
+  bool same(int B_, int k_, const std::vector<int>& par, const std::vector<int>& rk,
+            const std::vector<uint8_t>& an) const {
+    return B == B_ && k == k_ && parent == par && rank == rk && anchor == an;
+  }
+};
+
+}  // namespace
+
+struct firp_ctx {
+  firp_model_desc d{};
+  int k = 0, l = 0, dtype = 0;
+  bool split = false;   // activations as hi/lo bf16 planes (MFMA projection)
+  int gemm_kind = 0;    // 0 plain, 1 MFMA
+  hipStream_t stream = nullptr;
+  // weights
+  const void* embed = nullptr;
+  const void* norm_final = nullptr;
+  const void* lm_head = nullptr;
+  std::vector<const void*> wq, wk, wv, wo, wg, wu, wd, n1, n2, pw, pb;
+  // geometry
+  int Rmax = 0, Rpad = 0, slots = 0, qkv_ld = 0, esize = 0;
+  size_t kv_layer_stride = 0, kv_seq_stride = 0;
+  // device buffers
+  float* x = nullptr;
+  float* part = nullptr;
+  size_t part_elems = 0;
+  float* logits = nullptr;
+  Act act_d{}, act_q{}, act_o{}, act_f{}, act_p{};
+  void* kcache = nullptr;
+  void* vcache = nullptr;
+  int *rt_seq = nullptr, *rt_local = nullptr, *rt_pos = nullptr;
+  unsigned long long* rt_mask = nullptr;
+  int *tt_parent = nullptr, *tt_level = nullptr, *tt_rank = nullptr, *tt_cstart = nullptr,
+      *tt_clist = nullptr, *tt_pbase = nullptr, *pseudo_src = nullptr, *injected = nullptr;
+  SeqState st{};
+  // host state
+  int batch = 0;
+  bool prefilled = false;
+  std::vector<int> p0, drafts_valid;
+  HostTree cur;          // topology whose tables are on the device
+  bool tables_valid = false;
+  int last_rows = 0, last_N = 0, last_P = 0;
+  int* h_result = nullptr;  // pinned when a device is present
+  bool h_result_pinned = true;
+  std::string err;
+
+  firp_status fail(firp_status code, const char* fmt, ...) {
+    char buf[512];
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(buf, sizeof buf, fmt, ap);
+    va_end(ap);
+    err = buf;
+    return code;
+  }
+};
+
+namespace {
+
+bool desc_ok(const firp_model_desc* d, int k, std::string& why) {
+  auto bad = [&](const char* m) {
+    why = m;
+    return false;
+  };
+  if (!d) return bad("desc is NULL");
+  if (d->n_layers < 1 || d->d_model < 1 || d->n_q_heads < 1 || d->n_kv_heads < 1 || d->head_dim < 2 ||
+      d->d_ffn < 1 || d->vocab < 2)
+    return bad("non-positive model dimension");
+  if (d->head_dim % 2 || d->head_dim > 256) return bad("head_dim must be even and <= 256");
+  if (d->n_q_heads % d->n_kv_heads) return bad("n_q_heads must be a multiple of n_kv_heads");
+  if (d->dtype != FIRP_F32 && d->dtype != FIRP_BF16) return bad("unknown dtype");
+  if (!(d->rms_eps > 0.f) || !(d->rope_base > 1.f)) return bad("rms_eps / rope_base out of range");
+  if (d->max_ctx < 1 || d->max_batch < 1 || d->max_nodes < 1) return bad("non-positive capacity");
+  if (d->max_rows < d->max_nodes || d->max_rows > FIRP_MAX_ROWS) return bad("max_rows must be in [max_nodes, 256]");
+  if (d->b_max < 1 || d->b_max > FIRP_MAX_B || d->b_max > d->vocab) return bad("b_max out of range");
+  if (k < 0 || k > FIRP_MAX_K) return bad("k out of range");
+  return true;
+}
+
+// One carve-up serves firp_workspace_bytes (base == nullptr) and firp_init.
+size_t carve(firp_ctx* c, char* base) {
+  const firp_model_desc& d = c->d;
+  Carver cv{base};
+  int R = c->Rmax, Rp = c->Rpad;
+  size_t es = c->esize;
+  int qd = d.n_q_heads * d.head_dim;
+  c->x = cv.take<float>((size_t)Rp * d.d_model);
+  c->part = cv.take<float>(c->part_elems);
+  c->logits = cv.take<float>((size_t)Rp * d.vocab);
+  auto act = [&](Act& a, int ld) {
+    a.ld = ld;
+    a.f32 = cv.take<float>((size_t)Rp * ld);
+    a.hi = cv.take<bf16>((size_t)Rp * ld);
+    a.lo = cv.take<bf16>((size_t)Rp * ld);
+  };
+  act(c->act_d, d.d_model);
+  act(c->act_q, qd);
+  act(c->act_o, qd);
+  act(c->act_f, d.d_ffn);
+  act(c->act_p, d.d_model);
+  size_t kv_elems = (size_t)d.max_batch * c->kv_seq_stride;
+  c->kcache = cv.take<char>(kv_elems * es);
+  c->vcache = cv.take<char>(kv_elems * es);
+  c->rt_seq = cv.take<int>(R);
+  c->rt_local = cv.take<int>(R);
+  c->rt_pos = cv.take<int>(R);
+  c->rt_mask = cv.take<unsigned long long>((size_t)R * FIRP_MASK_WORDS);
+  int N = d.max_rows;  // prefill chunks use the node tables' row arrays only
+  c->tt_parent = cv.take<int>(N);
+  c->tt_level = cv.take<int>(N);
+  c->tt_rank = cv.take<int>(N);
+  c->tt_cstart = cv.take<int>(N + 1);
+  c->tt_clist = cv.take<int>(N);
+  c->tt_pbase = cv.take<int>(N);
+  c->pseudo_src = cv.take<int>(R);
+  c->injected = cv.take<int>(R);
+  int B = d.max_batch;
+  c->st.p0 = cv.take<int>(B);
+  c->st.root_tok = cv.take<int>(B);
+  c->st.drafts = cv.take<int>((size_t)B * std::max(c->k, 1) * d.b_max);
+  c->st.drafts_valid = cv.take<int>(B);
+  c->st.tok = cv.take<int>(R);
+  c->st.amax = cv.take<int>(R);
+  c->st.top = cv.take<int>((size_t)R * d.b_max);
+  c->st.result = cv.take<int>((size_t)B * FIRP_RESULT_STRIDE);
+  c->st.k = c->k;
+  c->st.b_max = d.b_max;
+  c->st.k_cap = FIRP_MAX_K;
+  return align_up(cv.off, 256);
+}
+
+void setup_geometry(firp_ctx* c, const firp_model_desc* d, int k) {
+  c->d = *d;
+  c->k = k;
+  c->dtype = d->dtype;
+  c->esize = d->dtype == FIRP_BF16 ? 2 : 4;
+  c->Rmax = d->max_batch * d->max_rows;
+  c->Rpad = (int)align_up(c->Rmax, 16);
+  c->slots = (int)align_up((size_t)d->max_ctx + d->max_rows, 64);
+  c->qkv_ld = (d->n_q_heads + 2 * d->n_kv_heads) * d->head_dim;
+  c->kv_layer_stride = (size_t)d->n_kv_heads * c->slots * d->head_dim;
+  c->kv_seq_stride = (size_t)d->n_layers * c->kv_layer_stride;
+  // split-K partial sums: the widest projection output times the largest split factor used
+  size_t widest = std::max<size_t>({(size_t)d->vocab, (size_t)2 * d->d_ffn, (size_t)c->qkv_ld, (size_t)d->d_model});
+  c->part_elems = (size_t)c->Rpad * widest * 8;
+}
+
+#define HIPCHK(call)                                                                         \
+  do {                                                                                       \
+    hipError_t e_ = (call);                                                                  \
+    if (e_ != hipSuccess) return c->fail(FIRP_EDEVICE, "%s failed: %s", #call, hipGetErrorString(e_)); \
+  } while (0)
+
+KvView kv_view(const firp_ctx* c, int layer) {
+  KvView v;
+  v.k = (char*)c->kcache + (size_t)layer * c->kv_layer_stride * c->esize;
+  v.v = (char*)c->vcache + (size_t)layer * c->kv_layer_stride * c->esize;
+  v.seq_stride = c->kv_seq_stride;
+  v.slots = c->slots;
+  v.n_kv_heads = c->d.n_kv_heads;
+  v.head_dim = c->d.head_dim;
+  return v;
+}
+
+RowTab row_tab(const firp_ctx* c) { return RowTab{c->rt_seq, c->rt_local, c->rt_pos, c->rt_mask}; }
+TreeTab tree_tab(const firp_ctx* c, int N, int P) {
+  return TreeTab{c->tt_parent, c->tt_level, c->tt_rank, c->tt_cstart, c->tt_clist, c->tt_pbase, N, P};
+}
+
+// y = act . W^T into the partial-sum buffer at column `col` of rows that are `ld` wide.
+// `like`: an earlier projection into the same rows whose split factor must be matched.
+Partial project(firp_ctx* c, const Act& in, const void* w, int rows, int n, int K, int ld, int col,
+                const Partial* like) {
+  Partial out;
+  out.ld = ld;
+  out.stride = (size_t)c->Rpad * ld;
+  out.p = c->part;
+  if (c->gemm_kind == 1 && gemm_mfma_supported(rows, n, K)) {
+    GemmPlan plan = gemm_mfma_plan(rows, n, K, like ? like->S : 0);
+    launch_gemm_mfma(in, (const bf16*)w, c->part + col, ld, out.stride, rows, n, K, plan, c->stream);
+    out.S = plan.S;
+  } else {
+    launch_gemm_simple(in.f32, in.ld, w, c->dtype, c->part + col, ld, rows, n, K, c->stream);
+    out.S = 1;
+  }
+  return out;
+}
+
+// The decoder over `rows_lo` rows for layers < l and `rows_hi` rows from layer l on.  With
+// `head`, ends with final norm, lm-head and argmax / top-b.
+firp_status forward(firp_ctx* c, int rows_lo, int rows_hi, int n_anchor_rows, int n_local_lo,
+                    int n_local_hi, int real_rows, bool head, int max_ctx_now) {
+  const firp_model_desc& d = c->d;
+  hipStream_t s = c->stream;
+  RowTab rt = row_tab(c);
+  const bool sp = c->split;
+  const int qd = d.n_q_heads * d.head_dim, kvd = d.n_kv_heads * d.head_dim;
+  launch_embed(c->embed, c->dtype, c->st.tok, rows_lo, d.d_model, c->x, s);
+  Partial pending{};  // projection output not yet added to the residual stream
+  int pending_rows = 0;
+  for (int layer = 0; layer <= d.n_layers; ++layer) {
+    int rows = layer < c->l ? rows_lo : rows_hi;
+    int n_local = layer < c->l ? n_local_lo : n_local_hi;
+    if (layer == c->l && rows_hi > rows_lo) {
+      // FIRP map (Eq. 3) on the raw residual stream of the anchor rows
+      if (pending.p) launch_add_partial(c->x, pending, pending_rows, d.d_model, s);
+      pending = Partial{};
+      launch_gather_rows(c->x, c->pseudo_src, n_anchor_rows, d.d_model, c->act_p, sp, s);
+      for (int i = 0; i < c->k; ++i) {
+        Partial y = project(c, c->act_p, c->pw[i], n_anchor_rows, d.d_model, d.d_model, d.d_model, 0, nullptr);
+        launch_scatter_pseudo(y, n_anchor_rows, d.d_model, c->k, i, c->pb.empty() ? nullptr : c->pb[i],
+                              c->dtype, c->x, rows_lo, s);
+      }
+    }
+    if (layer == d.n_layers) {
+      if (!head) {
+        if (pending.p) launch_add_partial(c->x, pending, pending_rows, d.d_model, s);
+        break;
+      }
+      launch_add_rmsnorm(c->x, pending, rows, d.d_model, c->norm_final, c->dtype, d.rms_eps, c->act_d, sp, s);
+      Partial lg = project(c, c->act_d, c->lm_head, rows, d.vocab, d.d_model, d.vocab, 0, nullptr);
+      launch_argmax_topb(lg, c->logits, real_rows, rows, d.vocab, d.b_max, c->st.amax, c->st.top, s);
+      break;
+    }
+    // the pending partials cover `pending_rows` rows; rows beyond (new pseudo rows) have none
+    if (pending.p && pending_rows < rows) {
+      launch_add_partial(c->x, pending, pending_rows, d.d_model, s);
+      pending = Partial{};
+    }
+    launch_add_rmsnorm(c->x, pending, rows, d.d_model, c->n1[layer], c->dtype, d.rms_eps, c->act_d, sp, s);
+    Partial q = project(c, c->act_d, c->wq[layer], rows, qd, d.d_model, c->qkv_ld, 0, nullptr);
+    project(c, c->act_d, c->wk[layer], rows, kvd, d.d_model, c->qkv_ld, qd, &q);
+    project(c, c->act_d, c->wv[layer], rows, kvd, d.d_model, c->qkv_ld, qd + kvd, &q);
+    KvView kv = kv_view(c, layer);
+    launch_rope_kv(q, rows, d.n_q_heads, rt, c->st.p0, d.rope_base, c->act_q, sp, kv, c->dtype, s);
+    launch_attention_simple(c->act_q, sp, rows, d.n_q_heads, rt, c->st.p0, kv, c->dtype, c->act_o, n_local,
+                            max_ctx_now + n_local, s);
+    Partial o = project(c, c->act_o, c->wo[layer], rows, d.d_model, qd, d.d_model, 0, nullptr);
+    launch_add_rmsnorm(c->x, o, rows, d.d_model, c->n2[layer], c->dtype, d.rms_eps, c->act_d, sp, s);
+    Partial g = project(c, c->act_d, c->wg[layer], rows, d.d_ffn, d.d_model, 2 * d.d_ffn, 0, nullptr);
+    project(c, c->act_d, c->wu[layer], rows, d.d_ffn, d.d_model, 2 * d.d_ffn, d.d_ffn, &g);
+    launch_swiglu(g, rows, d.d_ffn, c->act_f, sp, s);
+    pending = project(c, c->act_f, c->wd[layer], rows, d.d_model, d.d_ffn, d.d_model, 0, nullptr);
+    pending_rows = rows;
+  }
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return c->fail(FIRP_EDEVICE, "kernel launch failed: %s", hipGetErrorString(e));
+  return FIRP_OK;
+}
+
+// Host-side tree parser: depths, ancestor masks, child lists, pseudo-row table; uploads the
+// per-row and per-node tables for `B` sequences sharing the topology.
+firp_status upload_tree(firp_ctx* c, int B, const std::vector<int>& parent, const std::vector<int>& rank,
+                        const std::vector<uint8_t>& anchor) {
+  int N = (int)parent.size(), k = c->k;
+  if (c->tables_valid && c->cur.same(B, k, parent, rank, anchor)) return FIRP_OK;
+  std::vector<int> depth(N, 0), pbase(N, -1), cstart(N + 1, 0), clist(std::max(N - 1, 1), 0);
+  std::vector<std::vector<unsigned long long>> m(N, std::vector<unsigned long long>(FIRP_MASK_WORDS, 0));
+  int n_anchor = 0;
+  for (int v = 0; v < N; ++v) {
+    if (v > 0) {
+      depth[v] = depth[parent[v]] + 1;
+      m[v] = m[parent[v]];
+      cstart[parent[v] + 1]++;
+    }
+    m[v][v >> 6] |= 1ull << (v & 63);
+    if (anchor[v] && k > 0) pbase[v] = N + k * n_anchor++;
+  }
+  for (int v = 0; v < N; ++v) cstart[v + 1] += cstart[v];
+  {
+    std::vector<int> fill(cstart.begin(), cstart.end() - 1);
+    for (int v = 1; v < N; ++v) clist[fill[parent[v]]++] = v;  // ascending node id per parent
+  }
+  int P = k * n_anchor, T = N + P, R = B * T;
+  std::vector<int> seq(R), local(R), pos(R), psrc(std::max(B * n_anchor, 1));
+  std::vector<unsigned long long> mask((size_t)R * FIRP_MASK_WORDS);
+  for (int b = 0; b < B; ++b) {
+    for (int v = 0; v < N; ++v) {
+      int r = b * N + v;
+      seq[r] = b;
+      local[r] = v;
+      pos[r] = depth[v];
+      std::copy(m[v].begin(), m[v].end(), mask.begin() + (size_t)r * FIRP_MASK_WORDS);
+    }
+    int a_idx = 0;
+    for (int v = 0; v < N; ++v) {
+      if (pbase[v] < 0) continue;
+      psrc[b * n_anchor + a_idx] = b * N + v;
+      std::vector<unsigned long long> mm = m[v];
+      for (int i = 1; i <= k; ++i) {
+        int loc = pbase[v] + i - 1;
+        int r = B * N + b * P + (loc - N);
+        mm[loc >> 6] |= 1ull << (loc & 63);  // pseudo row i sees pseudo rows 1..i of its anchor
+        seq[r] = b;
+        local[r] = loc;
+        pos[r] = depth[v] + i;
+        std::copy(mm.begin(), mm.end(), mask.begin() + (size_t)r * FIRP_MASK_WORDS);
+      }
+      ++a_idx;
+    }
+  }
+  hipStream_t s = c->stream;
+  HIPCHK(hipStreamSynchronize(s));  // the previous step may still read the old tables
+  HIPCHK(hipMemcpy(c->rt_seq, seq.data(), R * sizeof(int), hipMemcpyHostToDevice));
+  HIPCHK(hipMemcpy(c->rt_local, local.data(), R * sizeof(int), hipMemcpyHostToDevice));
+  HIPCHK(hipMemcpy(c->rt_pos, pos.data(), R * sizeof(int), hipMemcpyHostToDevice));
+  HIPCHK(hipMemcpy(c->rt_mask, mask.data(), mask.size() * sizeof(unsigned long long), hipMemcpyHostToDevice));
+  HIPCHK(hipMemcpy(c->tt_parent, parent.data(), N * sizeof(int), hipMemcpyHostToDevice));
+  HIPCHK(hipMemcpy(c->tt_level, depth.data(), N * sizeof(int), hipMemcpyHostToDevice));
+  HIPCHK(hipMemcpy(c->tt_rank, rank.data(), N * sizeof(int), hipMemcpyHostToDevice));
+  HIPCHK(hipMemcpy(c->tt_cstart, cstart.data(), (N + 1) * sizeof(int), hipMemcpyHostToDevice));
+  HIPCHK(hipMemcpy(c->tt_clist, clist.data(), clist.size() * sizeof(int), hipMemcpyHostToDevice));
+  HIPCHK(hipMemcpy(c->tt_pbase, pbase.data(), N * sizeof(int), hipMemcpyHostToDevice));
+  HIPCHK(hipMemcpy(c->pseudo_src, psrc.data(), psrc.size() * sizeof(int), hipMemcpyHostToDevice));
+  c->cur.B = B;
+  c->cur.N = N;
+  c->cur.P = P;
+  c->cur.k = k;
+  c->cur.n_anchor = n_anchor;
+  c->cur.parent = parent;
+  c->cur.rank = rank;
+  c->cur.anchor = anchor;
+  c->cur.depth = depth;
+  c->cur.max_depth = *std::max_element(depth.begin(), depth.end());
+  c->tables_valid = true;
+  return FIRP_OK;
+}
+
+firp_status check_tree(firp_ctx* c, const firp_tree* t, bool injected, std::vector<int>& parent,
+                       std::vector<int>& rank, std::vector<uint8_t>& anchor, int& max_depth) {
+  if (!t || !t->parent || (t->n_nodes > 1 && !t->rank)) return c->fail(FIRP_EINVAL, "tree or its arrays are NULL");
+  int N = t->n_nodes;
+  if (N < 1) return c->fail(FIRP_EINVAL, "tree has no root");
+  if (N > c->d.max_nodes) return c->fail(FIRP_ECAPACITY, "tree has %d nodes, max_nodes is %d", N, c->d.max_nodes);
+  if (t->parent[0] != -1) return c->fail(FIRP_EINVAL, "parent[0] must be -1");
+  parent.assign(t->parent, t->parent + N);
+  rank.assign(N, 0);
+  anchor.assign(N, 1);
+  std::vector<int> depth(N, 0);
+  max_depth = 0;
+  int n_anchor = 0;
+  for (int v = 0; v < N; ++v) {
+    if (v > 0) {
+      if (parent[v] < 0 || parent[v] >= v) return c->fail(FIRP_EINVAL, "parent[%d] = %d is not an earlier node", v, parent[v]);
+      rank[v] = t->rank[v];
+      if (rank[v] < 0 || rank[v] >= c->d.b_max) return c->fail(FIRP_EINVAL, "rank[%d] = %d outside [0, b_max)", v, rank[v]);
+      depth[v] = depth[parent[v]] + 1;
+      max_depth = std::max(max_depth, depth[v]);
+    }
+    if (t->anchor) anchor[v] = t->anchor[v] ? 1 : 0;
+    if (c->k == 0) anchor[v] = 0;
+    n_anchor += anchor[v];
+  }
+  if (max_depth > FIRP_MAX_K) return c->fail(FIRP_EINVAL, "tree is %d levels deep, at most %d are supported", max_depth, FIRP_MAX_K);
+  (void)injected;
+  int T = N + c->k * n_anchor;
+  if (T > c->d.max_rows) return c->fail(FIRP_ECAPACITY, "step needs %d rows (N + k*anchors), max_rows is %d", T, c->d.max_rows);
+  return FIRP_OK;
+}
+
+firp_status run_step(firp_ctx* c, const firp_tree* tree, const int32_t* node_tokens, int32_t* accepted,
+                     int32_t* n_accepted) {
+  if (!c) return FIRP_EINVAL;
+  if (!accepted || !n_accepted) return c->fail(FIRP_EINVAL, "output pointer is NULL");
+  if (!c->prefilled) return c->fail(FIRP_ESTATE, "firp_step before firp_prefill");
+  std::vector<int> parent, rank;
+  std::vector<uint8_t> anchor;
+  int max_depth = 0;
+  firp_status st = check_tree(c, tree, node_tokens != nullptr, parent, rank, anchor, max_depth);
+  if (st != FIRP_OK) return st;
+  int B = c->batch;
+  int N_in = (int)parent.size();
+  bool any_valid = false;
+  for (int b = 0; b < B; ++b) any_valid |= c->drafts_valid[b] != 0;
+  if (!node_tokens && !any_valid && N_in > 1) {
+    // no sequence has drafts: the step degenerates to the root-only sub-tree
+    parent = {-1};
+    rank = {0};
+    anchor = {anchor[0]};
+    max_depth = 0;
+  }
+  int N = (int)parent.size();
+  int n_anchor = 0;
+  for (auto a : anchor) n_anchor += a;
+  int P = c->k * n_anchor, T = N + P;
+  int ctx_max = 0;
+  for (int b = 0; b < B; ++b) {
+    if (c->p0[b] + max_depth + 1 > c->d.max_ctx)
+      return c->fail(FIRP_ECAPACITY, "sequence %d: %d cached + %d new tokens exceed max_ctx %d", b, c->p0[b], max_depth + 1, c->d.max_ctx);
+    ctx_max = std::max(ctx_max, c->p0[b]);
+  }
+  if ((size_t)(c->d.head_dim + ctx_max + T) * sizeof(float) > 64 * 1024)
+    return c->fail(FIRP_ECAPACITY, "context of %d tokens exceeds the plain attention kernel's limit", ctx_max);
+  st = upload_tree(c, B, parent, rank, anchor);
+  if (st != FIRP_OK) return st;
+  hipStream_t s = c->stream;
+  const int* inj = nullptr;
+  if (node_tokens) {
+    if (N != N_in) return c->fail(FIRP_EINVAL, "internal: injected tokens with a substituted tree");
+    HIPCHK(hipMemcpyAsync(c->injected, node_tokens, (size_t)B * N * sizeof(int), hipMemcpyHostToDevice, s));
+    inj = c->injected;
+  }
+  launch_fill_tokens(c->st, tree_tab(c, N, P), B, inj, s);
+  st = forward(c, B * N, B * T, B * n_anchor, N, T, B * N, true, ctx_max);
+  if (st != FIRP_OK) return st;
+  launch_verify_select(c->st, tree_tab(c, N, P), B, s);
+  launch_kv_compact(kv_view(c, 0), c->kv_layer_stride, c->d.n_layers, B, c->st, c->dtype, s);
+  HIPCHK(hipMemcpyAsync(c->h_result, c->st.result, (size_t)B * FIRP_RESULT_STRIDE * sizeof(int), hipMemcpyDeviceToHost, s));
+  HIPCHK(hipStreamSynchronize(s));
+  for (int b = 0; b < B; ++b) {
+    const int* r = c->h_result + b * FIRP_RESULT_STRIDE;
+    n_accepted[b] = r[0];
+    for (int j = 0; j < r[0]; ++j) accepted[b * (FIRP_MAX_K + 1) + j] = r[3 + j];
+    c->drafts_valid[b] = r[1];
+    c->p0[b] = r[2] + r[0];
+  }
+  c->last_rows = B * T;
+  c->last_N = N;
+  c->last_P = P;
+  return FIRP_OK;
+}
+
+}  // namespace
+
+// ============================================================================ C ABI
+
+extern "C" {
+
+size_t firp_workspace_bytes(const firp_model_desc* desc, int32_t k) {
+  std::string why;
+  if (!desc_ok(desc, k, why)) return 0;
+  firp_ctx tmp;
+  setup_geometry(&tmp, desc, k);
+  return carve(&tmp, nullptr);
+}
+
+firp_status firp_init(firp_ctx** out, const firp_model_desc* desc, const firp_weights* w,
+                      const void* const* proj_w, const void* const* proj_b, int32_t layer_l, int32_t k,
+                      void* workspace, size_t workspace_bytes, void* hip_stream) {
+  auto bad = [&](firp_status code, const std::string& m) {
+    g_init_error = m;
+    return code;
+  };
+  if (!out) return bad(FIRP_EINVAL, "out is NULL");
+  *out = nullptr;
+  std::string why;
+  if (!desc_ok(desc, k, why)) return bad(FIRP_EINVAL, why);
+  if (layer_l < 0 || layer_l > desc->n_layers) return bad(FIRP_EINVAL, "layer_l outside [0, n_layers]");
+  if (!w || !w->embed || !w->wq || !w->wk || !w->wv || !w->wo || !w->w_gate || !w->w_up || !w->w_down ||
+      !w->norm_attn || !w->norm_mlp || !w->norm_final || !w->lm_head)
+    return bad(FIRP_EINVAL, "a weight pointer is NULL");
+  for (int i = 0; i < desc->n_layers; ++i)
+    if (!w->wq[i] || !w->wk[i] || !w->wv[i] || !w->wo[i] || !w->w_gate[i] || !w->w_up[i] || !w->w_down[i] ||
+        !w->norm_attn[i] || !w->norm_mlp[i])
+      return bad(FIRP_EINVAL, "a per-layer weight pointer is NULL");
+  if (k > 0) {
+    if (!proj_w) return bad(FIRP_EINVAL, "proj_w is NULL with k > 0");
+    for (int i = 0; i < k; ++i)
+      if (!proj_w[i] || (proj_b && !proj_b[i])) return bad(FIRP_EINVAL, "a projection pointer is NULL");
+  }
+  if (!workspace) return bad(FIRP_EINVAL, "workspace is NULL");
+  if (((uintptr_t)workspace) & 255) return bad(FIRP_EINVAL, "workspace is not 256-byte aligned");
+  firp_ctx* c = new firp_ctx;
+  setup_geometry(c, desc, k);
+  c->l = layer_l;
+  size_t need = carve(c, (char*)workspace);
+  if (workspace_bytes < need) {
+    delete c;
+    return bad(FIRP_ECAPACITY, "workspace too small");
+  }
+  c->stream = (hipStream_t)hip_stream;
+  c->embed = w->embed;
+  c->norm_final = w->norm_final;
+  c->lm_head = w->lm_head;
+  int L = desc->n_layers;
+  c->wq.assign(w->wq, w->wq + L);
+  c->wk.assign(w->wk, w->wk + L);
+  c->wv.assign(w->wv, w->wv + L);
+  c->wo.assign(w->wo, w->wo + L);
+  c->wg.assign(w->w_gate, w->w_gate + L);
+  c->wu.assign(w->w_up, w->w_up + L);
+  c->wd.assign(w->w_down, w->w_down + L);
+  c->n1.assign(w->norm_attn, w->norm_attn + L);
+  c->n2.assign(w->norm_mlp, w->norm_mlp + L);
+  if (k > 0) {
+    c->pw.assign(proj_w, proj_w + k);
+    if (proj_b) c->pb.assign(proj_b, proj_b + k);
+  }
+  c->gemm_kind = 0;
+  c->split = false;
+  c->p0.assign(desc->max_batch, 0);
+  c->drafts_valid.assign(desc->max_batch, 0);
+  size_t res_bytes = (size_t)desc->max_batch * FIRP_RESULT_STRIDE * sizeof(int);
+  if (hipHostMalloc((void**)&c->h_result, res_bytes, hipHostMallocDefault) != hipSuccess) {
+    // no usable device (host-only validation runs): an ordinary buffer keeps the context usable
+    (void)hipGetLastError();
+    c->h_result = (int*)calloc(1, res_bytes);
+    c->h_result_pinned = false;
+  }
+  *out = c;
+  return FIRP_OK;
+}
+
+firp_status firp_reset(firp_ctx* c) {
+  if (!c) return FIRP_EINVAL;
+  c->prefilled = false;
+  c->batch = 0;
+  std::fill(c->p0.begin(), c->p0.end(), 0);
+  std::fill(c->drafts_valid.begin(), c->drafts_valid.end(), 0);
+  return FIRP_OK;
+}
+
+void firp_destroy(firp_ctx* c) {
+  if (!c) return;
+  if (c->h_result) {
+    if (c->h_result_pinned)
+      (void)hipHostFree(c->h_result);
+    else
+      free(c->h_result);
+  }
+  delete c;
+}
+
+const char* firp_last_error(const firp_ctx* c) { return c ? c->err.c_str() : g_init_error.c_str(); }
+
+firp_status firp_prefill(firp_ctx* c, int32_t batch, const int32_t* tokens, const int32_t* lens,
+                         int32_t* first_token) {
+  if (!c) return FIRP_EINVAL;
+  if (!tokens || !lens || !first_token) return c->fail(FIRP_EINVAL, "argument pointer is NULL");
+  if (batch < 1 || batch > c->d.max_batch) return c->fail(FIRP_ECAPACITY, "batch %d outside [1, %d]", batch, c->d.max_batch);
+  size_t total = 0;
+  int longest = 0;
+  for (int b = 0; b < batch; ++b) {
+    if (lens[b] < 1) return c->fail(FIRP_EINVAL, "prompt %d is empty", b);
+    if (lens[b] > c->d.max_ctx) return c->fail(FIRP_ECAPACITY, "prompt %d has %d tokens, max_ctx is %d", b, lens[b], c->d.max_ctx);
+    longest = std::max(longest, lens[b]);
+    total += lens[b];
+  }
+  for (size_t i = 0; i < total; ++i)
+    if (tokens[i] < 0 || tokens[i] >= c->d.vocab) return c->fail(FIRP_EINVAL, "token %zu = %d outside the vocabulary", i, tokens[i]);
+  int C = c->d.max_rows;
+  if ((size_t)(c->d.head_dim + longest + C) * sizeof(float) > 64 * 1024)
+    return c->fail(FIRP_ECAPACITY, "prompt of %d tokens exceeds the plain attention kernel's limit", longest);
+  hipStream_t s = c->stream;
+  c->prefilled = false;
+  c->tables_valid = false;
+  // prompt[:-1] through the decoder in chunks: a chunk is a chain whose mask is lower-triangular
+  std::vector<int> seq(C), local(C), pos(C);
+  std::vector<unsigned long long> mask((size_t)C * FIRP_MASK_WORDS, 0);
+  for (int j = 0; j < C; ++j) {
+    local[j] = pos[j] = j;
+    for (int i = 0; i <= j; ++i) mask[(size_t)j * FIRP_MASK_WORDS + (i >> 6)] |= 1ull << (i & 63);
+  }
+  HIPCHK(hipStreamSynchronize(s));
+  HIPCHK(hipMemcpy(c->rt_local, local.data(), C * sizeof(int), hipMemcpyHostToDevice));
+  HIPCHK(hipMemcpy(c->rt_pos, pos.data(), C * sizeof(int), hipMemcpyHostToDevice));
+  HIPCHK(hipMemcpy(c->rt_mask, mask.data(), mask.size() * sizeof(unsigned long long), hipMemcpyHostToDevice));
+  const int32_t* tk = tokens;
+  for (int b = 0; b < batch; ++b) {
+    std::fill(seq.begin(), seq.end(), b);
+    HIPCHK(hipStreamSynchronize(s));
+    HIPCHK(hipMemcpy(c->rt_seq, seq.data(), C * sizeof(int), hipMemcpyHostToDevice));
+    launch_set_root(c->st, b, tk[lens[b] - 1], 0, s);
+    int done = 0, todo = lens[b] - 1;
+    while (done < todo) {
+      int n = std::min(C, todo - done);
+      HIPCHK(hipMemcpyAsync(c->st.tok, tk + done, n * sizeof(int), hipMemcpyHostToDevice, s));
+      firp_status st = forward(c, n, n, 0, n, n, n, false, done);
+      if (st != FIRP_OK) return st;
+      launch_advance_by(c->st.p0, b, n, s);
+      HIPCHK(hipStreamSynchronize(s));  // the token staging buffer is reused by the next chunk
+      done += n;
+    }
+    c->p0[b] = todo;
+    c->drafts_valid[b] = 0;
+    tk += lens[b];
+  }
+  c->batch = batch;
+  c->prefilled = true;
+  // root-only step on the last prompt token: first generated token and first drafts
+  int32_t par = -1, rk = 0;
+  uint8_t an = 1;
+  firp_tree root{1, &par, &rk, &an};
+  std::vector<int32_t> acc((size_t)batch * (FIRP_MAX_K + 1)), nacc(batch);
+  firp_status st = run_step(c, &root, nullptr, acc.data(), nacc.data());
+  if (st != FIRP_OK) {
+    c->prefilled = false;
+    return st;
+  }
+  for (int b = 0; b < batch; ++b) first_token[b] = acc[(size_t)b * (FIRP_MAX_K + 1)];
+  return FIRP_OK;
+}
+
+firp_status firp_step(firp_ctx* c, const firp_tree* tree, int32_t* accepted, int32_t* n_accepted) {
+  return run_step(c, tree, nullptr, accepted, n_accepted);
+}
+
+firp_status firp_step_with_candidates(firp_ctx* c, const firp_tree* tree, const int32_t* node_tokens,
+                                      int32_t* accepted, int32_t* n_accepted) {
+  if (!c) return FIRP_EINVAL;
+  if (!node_tokens) return c->fail(FIRP_EINVAL, "node_tokens is NULL");
+  if (tree && tree->n_nodes >= 1 && tree->n_nodes <= c->d.max_nodes)
+    for (int i = 0; i < c->batch * tree->n_nodes; ++i)
+      if (i % tree->n_nodes && (node_tokens[i] < -1 || node_tokens[i] >= c->d.vocab))
+        return c->fail(FIRP_EINVAL, "candidate %d = %d outside the vocabulary", i, node_tokens[i]);
+  return run_step(c, tree, node_tokens, accepted, n_accepted);
+}
+
+firp_status firp_check_tree(firp_ctx* c, const firp_tree* tree, int32_t* n_rows) {
+  if (!c) return FIRP_EINVAL;
+  std::vector<int> parent, rank;
+  std::vector<uint8_t> anchor;
+  int max_depth = 0;
+  firp_status st = check_tree(c, tree, false, parent, rank, anchor, max_depth);
+  if (st != FIRP_OK) return st;
+  int n_anchor = 0;
+  for (auto a : anchor) n_anchor += a;
+  if (n_rows) *n_rows = (int)parent.size() + c->k * n_anchor;
+  return FIRP_OK;
+}
+
+firp_status firp_debug_last_logits(firp_ctx* c, float* logits, int32_t* n_rows) {
+  if (!c) return FIRP_EINVAL;
+  if (!logits || !n_rows) return c->fail(FIRP_EINVAL, "argument pointer is NULL");
+  if (!c->prefilled || c->last_rows == 0) return c->fail(FIRP_ESTATE, "no step has run");
+  int B = c->batch, N = c->last_N, P = c->last_P, T = N + P, V = c->d.vocab;
+  HIPCHK(hipStreamSynchronize(c->stream));
+  for (int b = 0; b < B; ++b) {
+    HIPCHK(hipMemcpy(logits + ((size_t)b * T) * V, c->logits + ((size_t)b * N) * V, (size_t)N * V * sizeof(float), hipMemcpyDeviceToHost));
+    if (P)
+      HIPCHK(hipMemcpy(logits + ((size_t)b * T + N) * V, c->logits + ((size_t)B * N + (size_t)b * P) * V, (size_t)P * V * sizeof(float), hipMemcpyDeviceToHost));
+  }
+  *n_rows = T;
+  return FIRP_OK;
+}
+
+firp_status firp_debug_last_path(firp_ctx* c, int32_t* path_nodes) {
+  if (!c) return FIRP_EINVAL;
+  if (!path_nodes) return c->fail(FIRP_EINVAL, "argument pointer is NULL");
+  if (!c->prefilled || c->last_rows == 0) return c->fail(FIRP_ESTATE, "no step has run");
+  for (int b = 0; b < c->batch; ++b) {
+    const int* r = c->h_result + b * FIRP_RESULT_STRIDE;
+    for (int j = 0; j < r[0]; ++j) path_nodes[b * (FIRP_MAX_K + 1) + j] = r[3 + (FIRP_MAX_K + 1) + j];
+  }
+  return FIRP_OK;
+}
+
+firp_status firp_get_drafts(const firp_ctx* cc, int32_t* drafts, int32_t* valid) {
+  firp_ctx* c = const_cast<firp_ctx*>(cc);
+  if (!c) return FIRP_EINVAL;
+  if (!drafts || !valid) return c->fail(FIRP_EINVAL, "argument pointer is NULL");
+  if (!c->prefilled) return c->fail(FIRP_ESTATE, "no sequence is running");
+  HIPCHK(hipStreamSynchronize(c->stream));
+  if (c->k > 0)
+    HIPCHK(hipMemcpy(drafts, c->st.drafts, (size_t)c->batch * c->k * c->d.b_max * sizeof(int), hipMemcpyDeviceToHost));
+  for (int b = 0; b < c->batch; ++b) valid[b] = c->drafts_valid[b];
+  return FIRP_OK;
+}
+
+firp_status firp_get_ctx_len(const firp_ctx* cc, int32_t* len) {
+  firp_ctx* c = const_cast<firp_ctx*>(cc);
+  if (!c) return FIRP_EINVAL;
+  if (!len) return c->fail(FIRP_EINVAL, "argument pointer is NULL");
+  for (int b = 0; b < c->batch; ++b) len[b] = c->p0[b];
+  return FIRP_OK;
+}
+
+firp_status firp_debug_read_cache(firp_ctx* c, int32_t seq, int32_t layer, float* k_out, float* v_out) {
+  if (!c) return FIRP_EINVAL;
+  if (!k_out || !v_out) return c->fail(FIRP_EINVAL, "argument pointer is NULL");
+  if (!c->prefilled) return c->fail(FIRP_ESTATE, "no sequence is running");
+  if (seq < 0 || seq >= c->batch || layer < 0 || layer >= c->d.n_layers) return c->fail(FIRP_EINVAL, "sequence or layer out of range");
+  HIPCHK(hipStreamSynchronize(c->stream));
+  int len = c->p0[seq], H = c->d.n_kv_heads, dh = c->d.head_dim, S = c->slots, es = c->esize;
+  std::vector<char> hk((size_t)H * S * dh * es), hv((size_t)H * S * dh * es);
+  size_t off = ((size_t)seq * c->kv_seq_stride + (size_t)layer * c->kv_layer_stride) * es;
+  HIPCHK(hipMemcpy(hk.data(), (char*)c->kcache + off, hk.size(), hipMemcpyDeviceToHost));
+  HIPCHK(hipMemcpy(hv.data(), (char*)c->vcache + off, hv.size(), hipMemcpyDeviceToHost));
+  auto get = [&](const std::vector<char>& buf, size_t idx) -> float {
+    if (es == 4) return ((const float*)buf.data())[idx];
+    uint32_t u = ((uint32_t)((const uint16_t*)buf.data())[idx]) << 16;
+    float f;
+    memcpy(&f, &u, 4);
+    return f;
+  };
+  for (int t = 0; t < len; ++t)
+    for (int h = 0; h < H; ++h)
+      for (int e = 0; e < dh; ++e) {
+        k_out[((size_t)t * H + h) * dh + e] = get(hk, ((size_t)h * S + t) * dh + e);
+        v_out[((size_t)t * H + h) * dh + e] = get(hv, ((size_t)h * dh + e) * S + t);
+      }
+  return FIRP_OK;
+}
+
+firp_status firp_set_option(firp_ctx* c, const char* name, int32_t value) {
+  if (!c) return FIRP_EINVAL;
+  if (!name) return c->fail(FIRP_EINVAL, "option name is NULL");
+  if (!strcmp(name, "gemm")) {
+    if (value == 0) {
+      c->gemm_kind = 0;
+      c->split = false;
+      return FIRP_OK;
+    }
+    if (value == 1 && c->dtype == FIRP_BF16) {
+      c->gemm_kind = 1;
+      c->split = true;
+      return FIRP_OK;
+    }
+    return c->fail(FIRP_EINVAL, "gemm kind %d is not available for this model", value);
+  }
+  return c->fail(FIRP_EINVAL, "unknown option '%s'", name);
+}
+
+size_t firp_gemm_workspace_bytes(int32_t rows, int32_t n, int32_t k_dim) {
+  if (rows < 1 || n < 1 || k_dim < 1) return 0;
+  size_t rp = align_up(rows, 16);
+  return align_up(rp * k_dim * 2 * 2, 256) + align_up(rp * (size_t)n * 4 * 8, 256) + 512;
+}
+
+firp_status firp_debug_gemm(const float* x, const void* w, float* y, int32_t rows, int32_t n, int32_t k_dim,
+                            int32_t dtype, int32_t kind, void* workspace, size_t workspace_bytes,
+                            void* hip_stream) {
+  if (!x || !w || !y || rows < 1 || n < 1 || k_dim < 1) return FIRP_EINVAL;
+  if (dtype != FIRP_F32 && dtype != FIRP_BF16) return FIRP_EINVAL;
+  hipStream_t s = (hipStream_t)hip_stream;
+  if (kind == 0) {
+    launch_gemm_simple(x, k_dim, w, dtype, y, n, rows, n, k_dim, s);
+  } else if (kind == 1) {
+    if (dtype != FIRP_BF16 || !gemm_mfma_supported(rows, n, k_dim)) return FIRP_EINVAL;
+    if (!workspace || (((uintptr_t)workspace) & 255) || workspace_bytes < firp_gemm_workspace_bytes(rows, n, k_dim))
+      return FIRP_ECAPACITY;
+    size_t rp = align_up(rows, 16);
+    Act a{};
+    a.ld = k_dim;
+    a.hi = (bf16*)workspace;
+    a.lo = a.hi + rp * k_dim;
+    float* part = (float*)((char*)workspace + align_up(rp * k_dim * 2 * 2, 256));
+    launch_split_act(x, rows, k_dim, a, s);
+    GemmPlan plan = gemm_mfma_plan(rows, n, k_dim, 0);
+    launch_gemm_mfma(a, (const bf16*)w, part, n, rp * n, rows, n, k_dim, plan, s);
+    launch_reduce_partials(Partial{part, plan.S, rp * (size_t)n, n}, y, rows, s);
+  } else {
+    return FIRP_EINVAL;
+  }
+  return hipGetLastError() == hipSuccess ? FIRP_OK : FIRP_EDEVICE;
+}
+
+}  // extern "C"

@@ -1,0 +1,103 @@
+// Launchers of the step's kernels.  Everything is enqueued on the given stream; nothing here
+// synchronises or allocates.
+#pragma once
+#include "common.h"
+
+namespace firp {
+
+enum { DT_F32 = 0, DT_BF16 = 1 };
+
+// KV cache of one layer.  K: [B][Hkv][slots][dh]; V is stored transposed, [B][Hkv][dh][slots],
+// so that the P.V contraction reads keys contiguously.  seq_stride = elements between sequences.
+struct KvView {
+  void* k;
+  void* v;
+  size_t seq_stride;
+  int slots;  // per (sequence, head): max_ctx + step rows, multiple of 64
+  int n_kv_heads, head_dim;
+};
+
+// Node tables of the tree (device), shared by all sequences of a step.
+struct TreeTab {
+  const int* parent;
+  const int* level;       // depth of node v (root 0)
+  const int* rank;
+  const int* child_start; // CSR over children, [N+1]
+  const int* child_list;  // [N-1]
+  const int* pseudo_base; // local row of the first pseudo row of node v, or -1
+  int n_nodes;
+  int n_pseudo;           // pseudo rows per sequence
+};
+
+// Per-sequence decoding state (device).
+struct SeqState {
+  int* p0;           // [B] committed cache length
+  int* root_tok;     // [B] last emitted token = next root
+  int* drafts;       // [B][k][b_max]
+  int* drafts_valid; // [B]
+  int* tok;          // [B][N] token of every node of the running step
+  int* amax;         // [B*N] greedy token per real row
+  int* top;          // [B*P][b_max] top-b ids per pseudo row
+  int* result;       // [B][RESULT_STRIDE]: n_emitted, drafts_valid, p0 before, tokens[k_cap+1], path[k_cap+1]
+  int k, b_max, k_cap;
+};
+#define FIRP_RESULT_STRIDE 40
+#define FIRP_MAX_COMMIT 9   // deepest tree level + 1
+
+void launch_fill_tokens(const SeqState& st, const TreeTab& tt, int B, const int* injected,
+                        hipStream_t s);
+void launch_embed(const void* embed, int dtype, const int* tok, int rows, int d, float* x,
+                  hipStream_t s);
+// x[r] += sum of partials (if part.p), then act = rmsnorm(x[r]) * gain.
+void launch_add_rmsnorm(float* x, const Partial& part, int rows, int d, const void* gain,
+                        int dtype, float eps, const Act& out, bool split, hipStream_t s);
+// Only the residual update, no norm output (used before the projection at the FIRP layer).
+void launch_add_partial(float* x, const Partial& part, int rows, int d, hipStream_t s);
+// qkv partials -> rotary q (activation planes, [rows][Hq*dh]) and K / V^T into the cache.
+void launch_rope_kv(const Partial& qkv, int rows, int n_q_heads, const RowTab& rt, const int* p0,
+                    float rope_base, const Act& q_out, bool split, const KvView& kv, int dtype,
+                    hipStream_t s);
+void launch_swiglu(const Partial& gate_up, int rows, int d_ffn, const Act& out, bool split,
+                   hipStream_t s);
+// FIRP map (Eq. 3): gather anchor rows of the residual stream as projection input ...
+void launch_gather_rows(const float* x, const int* src_rows, int rows, int d, const Act& out,
+                        bool split, hipStream_t s);
+// ... and scatter map i's output (+ bias) to the pseudo rows.
+void launch_scatter_pseudo(const Partial& y, int n_anchor_rows, int d, int k, int i,
+                           const void* bias, int dtype, float* x, int first_pseudo_row,
+                           hipStream_t s);
+// greedy token of every real row and top-b of every pseudo row; also leaves summed logits.
+void launch_argmax_topb(const Partial& logits, float* logits_out, int real_rows, int rows,
+                        int vocab, int b_max, int* amax, int* top, hipStream_t s);
+void launch_verify_select(const SeqState& st, const TreeTab& tt, int B, hipStream_t s);
+// move the accepted path's K/V to the front of the step's slots; advances nothing.
+void launch_kv_compact(const KvView& kv_layer0, size_t layer_stride, int n_layers, int B,
+                       const SeqState& st, int dtype, hipStream_t s);
+void launch_advance_by(int* p0, int seq, int n, hipStream_t s);           // prefill chunk
+void launch_set_root(const SeqState& st, int seq, int token, int p0, hipStream_t s);
+
+// plain attention: every (row, head) walks its visible keys
+void launch_attention_simple(const Act& q, bool split, int rows, int n_q_heads, const RowTab& rt,
+                             const int* p0, const KvView& kv, int dtype, const Act& out,
+                             int n_local, int max_keys, hipStream_t s);
+
+// plain tiled projection: y[S=1][rows][n] = x_f32[rows][K] . W[n][K]^T
+void launch_gemm_simple(const float* x, int ldx, const void* w, int dtype, float* y, int ldy,
+                        int rows, int n, int K, hipStream_t s);
+
+// MFMA weight-streaming projection for bf16 weights; see gemm_mfma.hip
+struct GemmPlan {
+  int S;        // split-K factor
+  int k_per;    // K elements per split (multiple of 64)
+  int nt;       // 16-row activation tiles
+  int grid;
+};
+bool gemm_mfma_supported(int rows, int n, int K);
+GemmPlan gemm_mfma_plan(int rows, int n, int K, int force_split);  // force_split 0 = choose
+// partials[s][r][c] at out + s*part_stride + r*ld + c for c < n
+void launch_gemm_mfma(const Act& x, const bf16* w, float* out, int ld, size_t part_stride, int rows,
+                      int n, int K, const GemmPlan& plan, hipStream_t s);
+void launch_split_act(const float* x, int rows, int ld, const Act& out, hipStream_t s);
+void launch_reduce_partials(const Partial& p, float* y, int rows, hipStream_t s);
+
+}  // namespace firp

@@ -1,0 +1,409 @@
+// Everything of the step that is not a projection or attention: candidate fill, embedding
+// gather, fused residual-add + RMSNorm, rotary + KV append, SwiGLU, the FIRP map's gather /
+// scatter, argmax / top-b over the logits, greedy verification, KV compaction.
+#include "kernels.h"
+
+namespace firp {
+
+// ------------------------------------------------------------------------------------------
+// Candidate fill (Inference stage: the tree verified now was drafted by the previous step).
+// Node v at depth j carries drafts[j-1][rank[v]]; without valid drafts every candidate is -1,
+// which no greedy token equals, so the step accepts nothing beyond the root.
+__global__ void k_fill_tokens(SeqState st, TreeTab tt, const int* injected) {
+  int b = blockIdx.x;
+  for (int v = threadIdx.x; v < tt.n_nodes; v += blockDim.x) {
+    int t;
+    if (v == 0) {
+      t = st.root_tok[b];
+    } else if (injected) {
+      t = injected[b * tt.n_nodes + v];
+    } else {
+      int lvl = tt.level[v];
+      t = (st.drafts_valid[b] && lvl <= st.k) ? st.drafts[(b * st.k + lvl - 1) * st.b_max + tt.rank[v]] : -1;
+    }
+    st.tok[b * tt.n_nodes + v] = t;
+  }
+}
+
+void launch_fill_tokens(const SeqState& st, const TreeTab& tt, int B, const int* injected,
+                        hipStream_t s) {
+  hipLaunchKernelGGL(k_fill_tokens, dim3(B), dim3(64), 0, s, st, tt, injected);
+}
+
+// ------------------------------------------------------------------------------------------
+template <typename WT>
+__global__ void k_embed(const WT* __restrict__ E, const int* __restrict__ tok, int d, float* x) {
+  int r = blockIdx.x;
+  int t = tok[r];
+  if (t < 0) t = 0;
+  const WT* e = E + (size_t)t * d;
+  for (int i = threadIdx.x; i < d; i += blockDim.x) x[(size_t)r * d + i] = to_f32(e[i]);
+}
+
+void launch_embed(const void* embed, int dtype, const int* tok, int rows, int d, float* x,
+                  hipStream_t s) {
+  if (dtype == DT_BF16)
+    hipLaunchKernelGGL(k_embed<bf16>, dim3(rows), dim3(256), 0, s, (const bf16*)embed, tok, d, x);
+  else
+    hipLaunchKernelGGL(k_embed<float>, dim3(rows), dim3(256), 0, s, (const float*)embed, tok, d, x);
+}
+
+// ------------------------------------------------------------------------------------------
+// Residual update + RMSNorm: x[r] += sum_s part[s][r]; act[r] = x[r] / sqrt(mean(x^2)+eps) * g.
+template <typename GT, bool SPLIT, bool NORM>
+__global__ __launch_bounds__(256) void k_add_rmsnorm(float* x, Partial part, int d,
+                                                     const GT* __restrict__ gain, float eps, Act out) {
+  __shared__ float red[4];
+  int r = blockIdx.x;
+  float* xr = x + (size_t)r * d;
+  float ss = 0.f;
+  for (int i = threadIdx.x; i < d; i += 256) {
+    float v = xr[i];
+    if (part.p) {
+      v += partial_sum(part, (size_t)r * part.ld + i);
+      xr[i] = v;
+    }
+    ss += v * v;
+  }
+  if constexpr (NORM) {
+    ss = block_sum_256(ss, red);
+    float inv = 1.0f / sqrtf(ss / (float)d + eps);
+    for (int i = threadIdx.x; i < d; i += 256)
+      act_store<SPLIT>(out, (size_t)r * out.ld + i, xr[i] * inv * to_f32(gain[i]));
+  }
+}
+
+void launch_add_rmsnorm(float* x, const Partial& part, int rows, int d, const void* gain,
+                        int dtype, float eps, const Act& out, bool split, hipStream_t s) {
+  dim3 g(rows), b(256);
+  if (dtype == DT_BF16) {
+    if (split)
+      hipLaunchKernelGGL((k_add_rmsnorm<bf16, true, true>), g, b, 0, s, x, part, d, (const bf16*)gain, eps, out);
+    else
+      hipLaunchKernelGGL((k_add_rmsnorm<bf16, false, true>), g, b, 0, s, x, part, d, (const bf16*)gain, eps, out);
+  } else {
+    hipLaunchKernelGGL((k_add_rmsnorm<float, false, true>), g, b, 0, s, x, part, d, (const float*)gain, eps, out);
+  }
+}
+
+void launch_add_partial(float* x, const Partial& part, int rows, int d, hipStream_t s) {
+  Act none{};
+  hipLaunchKernelGGL((k_add_rmsnorm<float, false, false>), dim3(rows), dim3(256), 0, s, x, part, d,
+                     (const float*)nullptr, 0.f, none);
+}
+
+// ------------------------------------------------------------------------------------------
+// Rotary embedding (half-split pairs (j, j+dh/2), angle pos * base^(-2j/dh)) on q and k at the
+// row's position id p0 + pos_off (tree nodes keep their original positions; siblings share
+// one), then K and V^T go to cache slot p0 + local.  The angle is formed in fp64: at positions
+// in the thousands an fp32 product would already be off by 1e-4 rad.
+template <typename KT, bool SPLIT>
+__global__ void k_rope_kv(Partial qkv, int n_q_heads, RowTab rt, const int* __restrict__ p0,
+                          float rope_base, Act q_out, KvView kv) {
+  int r = blockIdx.x, h = blockIdx.y, j = threadIdx.x;
+  int dh = kv.head_dim, half = dh >> 1, Hkv = kv.n_kv_heads;
+  int b = rt.seq[r];
+  int base_pos = p0[b];
+  size_t row_off = (size_t)r * qkv.ld;
+  if (h < n_q_heads + Hkv) {
+    double inv_freq = exp2(-2.0 * (double)j / (double)dh * log2((double)rope_base));
+    double ang = (double)(base_pos + rt.pos_off[r]) * inv_freq;
+    double sd, cd;
+    sincos(ang, &sd, &cd);
+    float c = (float)cd, sn = (float)sd;
+    float x1 = partial_sum(qkv, row_off + (size_t)h * dh + j);
+    float x2 = partial_sum(qkv, row_off + (size_t)h * dh + j + half);
+    float y1 = x1 * c - x2 * sn, y2 = x2 * c + x1 * sn;
+    if (h < n_q_heads) {
+      act_store<SPLIT>(q_out, (size_t)r * q_out.ld + (size_t)h * dh + j, y1);
+      act_store<SPLIT>(q_out, (size_t)r * q_out.ld + (size_t)h * dh + j + half, y2);
+    } else {
+      int hk = h - n_q_heads;
+      size_t slot = (size_t)(base_pos + rt.local[r]);
+      KT* krow = (KT*)kv.k + (size_t)b * kv.seq_stride + ((size_t)hk * kv.slots + slot) * dh;
+      store_elt<KT>(krow + j, y1);
+      store_elt<KT>(krow + j + half, y2);
+    }
+  } else {
+    int hv = h - n_q_heads - Hkv;
+    size_t slot = (size_t)(base_pos + rt.local[r]);
+    KT* vt = (KT*)kv.v + (size_t)b * kv.seq_stride + (size_t)hv * dh * kv.slots + slot;
+    float v1 = partial_sum(qkv, row_off + (size_t)(n_q_heads + Hkv + hv) * dh + j);
+    float v2 = partial_sum(qkv, row_off + (size_t)(n_q_heads + Hkv + hv) * dh + j + half);
+    store_elt<KT>(vt + (size_t)j * kv.slots, v1);
+    store_elt<KT>(vt + (size_t)(j + half) * kv.slots, v2);
+  }
+}
+
+void launch_rope_kv(const Partial& qkv, int rows, int n_q_heads, const RowTab& rt, const int* p0,
+                    float rope_base, const Act& q_out, bool split, const KvView& kv, int dtype,
+                    hipStream_t s) {
+  dim3 g(rows, n_q_heads + 2 * kv.n_kv_heads), b(kv.head_dim / 2);
+  if (dtype == DT_BF16) {
+    if (split)
+      hipLaunchKernelGGL((k_rope_kv<bf16, true>), g, b, 0, s, qkv, n_q_heads, rt, p0, rope_base, q_out, kv);
+    else
+      hipLaunchKernelGGL((k_rope_kv<bf16, false>), g, b, 0, s, qkv, n_q_heads, rt, p0, rope_base, q_out, kv);
+  } else {
+    hipLaunchKernelGGL((k_rope_kv<float, false>), g, b, 0, s, qkv, n_q_heads, rt, p0, rope_base, q_out, kv);
+  }
+}
+
+// ------------------------------------------------------------------------------------------
+// SwiGLU: act = silu(gate) * up, gate = columns [0,F), up = columns [F,2F) of the partials.
+template <bool SPLIT>
+__global__ void k_swiglu(Partial gu, int F, Act out) {
+  int r = blockIdx.y;
+  int j = blockIdx.x * blockDim.x + threadIdx.x;
+  if (j >= F) return;
+  float g = partial_sum(gu, (size_t)r * gu.ld + j);
+  float u = partial_sum(gu, (size_t)r * gu.ld + F + j);
+  float sg = g / (1.0f + expf(-g));
+  act_store<SPLIT>(out, (size_t)r * out.ld + j, sg * u);
+}
+
+void launch_swiglu(const Partial& gate_up, int rows, int d_ffn, const Act& out, bool split,
+                   hipStream_t s) {
+  dim3 g((d_ffn + 255) / 256, rows), b(256);
+  if (split)
+    hipLaunchKernelGGL(k_swiglu<true>, g, b, 0, s, gate_up, d_ffn, out);
+  else
+    hipLaunchKernelGGL(k_swiglu<false>, g, b, 0, s, gate_up, d_ffn, out);
+}
+
+// ------------------------------------------------------------------------------------------
+// FIRP map, Eq. 3: pseudo hidden state i of anchor a is W_i x_a + b_i on the raw residual
+// stream.  gather: rows of x -> projection input; scatter: projection output (+bias) -> x.
+template <bool SPLIT>
+__global__ void k_gather_rows(const float* __restrict__ x, const int* __restrict__ src, int d, Act out) {
+  int g = blockIdx.x;
+  const float* xr = x + (size_t)src[g] * d;
+  for (int i = threadIdx.x; i < d; i += blockDim.x) act_store<SPLIT>(out, (size_t)g * out.ld + i, xr[i]);
+}
+
+void launch_gather_rows(const float* x, const int* src_rows, int rows, int d, const Act& out,
+                        bool split, hipStream_t s) {
+  if (split)
+    hipLaunchKernelGGL(k_gather_rows<true>, dim3(rows), dim3(256), 0, s, x, src_rows, d, out);
+  else
+    hipLaunchKernelGGL(k_gather_rows<false>, dim3(rows), dim3(256), 0, s, x, src_rows, d, out);
+}
+
+template <typename BT>
+__global__ void k_scatter_pseudo(Partial y, int d, int k, int i, const BT* __restrict__ bias, float* x,
+                                 int first_pseudo_row) {
+  int g = blockIdx.x;
+  float* xr = x + (size_t)(first_pseudo_row + g * k + i) * d;
+  for (int c = threadIdx.x; c < d; c += blockDim.x) {
+    float v = partial_sum(y, (size_t)g * y.ld + c);
+    if (bias) v += to_f32(bias[c]);
+    xr[c] = v;
+  }
+}
+
+void launch_scatter_pseudo(const Partial& y, int n_anchor_rows, int d, int k, int i,
+                           const void* bias, int dtype, float* x, int first_pseudo_row,
+                           hipStream_t s) {
+  if (dtype == DT_BF16)
+    hipLaunchKernelGGL(k_scatter_pseudo<bf16>, dim3(n_anchor_rows), dim3(256), 0, s, y, d, k, i,
+                       (const bf16*)bias, x, first_pseudo_row);
+  else
+    hipLaunchKernelGGL(k_scatter_pseudo<float>, dim3(n_anchor_rows), dim3(256), 0, s, y, d, k, i,
+                       (const float*)bias, x, first_pseudo_row);
+}
+
+// ------------------------------------------------------------------------------------------
+// Greedy token of real rows, top-b of pseudo rows.  Order: larger logit first, ties to the
+// lower token id.  One block per row; pass p finds the best entry that comes strictly after
+// the winner of pass p-1 in that order.
+struct Best {
+  float v;
+  int id;
+};
+__device__ __forceinline__ bool better(float v, int id, const Best& o) {
+  return v > o.v || (v == o.v && id < o.id);
+}
+
+__global__ __launch_bounds__(256) void k_argmax_topb(Partial lg, float* logits_out, int real_rows,
+                                                     int vocab, int b_max, int* amax, int* top) {
+  __shared__ float sv[256];
+  __shared__ int si[256];
+  int r = blockIdx.x;
+  size_t off = (size_t)r * lg.ld;
+  if (logits_out && (lg.S > 1 || logits_out != lg.p)) {
+    for (int t = threadIdx.x; t < vocab; t += 256) logits_out[(size_t)r * vocab + t] = partial_sum(lg, off + t);
+    __syncthreads();
+  }
+  const float* row = logits_out ? logits_out + (size_t)r * vocab : nullptr;
+  int passes = (r < real_rows) ? 1 : b_max;
+  Best prev{__builtin_inff(), -1};
+  for (int p = 0; p < passes; ++p) {
+    Best best{-__builtin_inff(), 0x7fffffff};
+    for (int t = threadIdx.x; t < vocab; t += 256) {
+      float v = row ? row[t] : partial_sum(lg, off + t);
+      bool after_prev = (p == 0) || v < prev.v || (v == prev.v && t > prev.id);
+      if (after_prev && better(v, t, best)) best = Best{v, t};
+    }
+    sv[threadIdx.x] = best.v;
+    si[threadIdx.x] = best.id;
+    __syncthreads();
+    for (int w = 128; w > 0; w >>= 1) {
+      if (threadIdx.x < w) {
+        Best o{sv[threadIdx.x + w], si[threadIdx.x + w]};
+        Best m{sv[threadIdx.x], si[threadIdx.x]};
+        if (better(o.v, o.id, m)) {
+          sv[threadIdx.x] = o.v;
+          si[threadIdx.x] = o.id;
+        }
+      }
+      __syncthreads();
+    }
+    prev = Best{sv[0], si[0]};
+    __syncthreads();
+    if (threadIdx.x == 0) {
+      if (r < real_rows)
+        amax[r] = prev.id;
+      else
+        top[(size_t)(r - real_rows) * b_max + p] = prev.id;
+    }
+  }
+}
+
+void launch_argmax_topb(const Partial& logits, float* logits_out, int real_rows, int rows,
+                        int vocab, int b_max, int* amax, int* top, hipStream_t s) {
+  hipLaunchKernelGGL(k_argmax_topb, dim3(rows), dim3(256), 0, s, logits, logits_out, real_rows, vocab,
+                     b_max, amax, top);
+}
+
+// ------------------------------------------------------------------------------------------
+// Greedy verification (Inference stage): from the root, emit the greedy token of the current
+// node and move to the child that carries it (lowest node id if several do); stop when none
+// does.  Then read the next drafts off the pseudo rows of the node that ends the path.
+__global__ void k_verify_select(SeqState st, TreeTab tt) {
+  int b = blockIdx.x;
+  int N = tt.n_nodes;
+  int* res = st.result + b * FIRP_RESULT_STRIDE;
+  __shared__ int s_cur;
+  if (threadIdx.x == 0) {
+    const int* tok = st.tok + b * N;
+    const int* amax = st.amax + b * N;
+    int cur = 0, n = 0;
+    int* out_tok = res + 3;
+    int* out_path = res + 3 + (st.k_cap + 1);
+    while (true) {
+      int t = amax[cur];
+      out_tok[n] = t;
+      out_path[n] = cur;
+      ++n;
+      int nxt = -1;
+      for (int e = tt.child_start[cur]; e < tt.child_start[cur + 1]; ++e) {
+        int c = tt.child_list[e];
+        if (tok[c] == t) {
+          nxt = c;
+          break;
+        }
+      }
+      if (nxt < 0 || n > st.k_cap) break;  // n <= k_cap + 1 by the depth check on the host
+      cur = nxt;
+    }
+    int pb = tt.pseudo_base[cur];
+    res[0] = n;
+    res[1] = (pb >= 0 && st.k > 0) ? 1 : 0;
+    res[2] = st.p0[b];  // cache length before this step's commit
+    st.p0[b] += n;
+    st.root_tok[b] = out_tok[n - 1];
+    st.drafts_valid[b] = res[1];
+    s_cur = cur;
+  }
+  __syncthreads();
+  int pb = tt.pseudo_base[s_cur];
+  if (pb >= 0 && st.k > 0) {
+    const int* src = st.top + ((size_t)b * tt.n_pseudo + (pb - N)) * st.b_max;
+    for (int e = threadIdx.x; e < st.k * st.b_max; e += blockDim.x) st.drafts[(size_t)b * st.k * st.b_max + e] = src[e];
+  }
+}
+
+void launch_verify_select(const SeqState& st, const TreeTab& tt, int B, hipStream_t s) {
+  hipLaunchKernelGGL(k_verify_select, dim3(B), dim3(64), 0, s, st, tt);
+}
+
+// ------------------------------------------------------------------------------------------
+// Commit: the accepted path's nodes sit at slots p0 + path[j]; move them to p0 + j.  Nodes are
+// in topological order so path[j] >= j: every destination lies at or before its source.  All
+// sources are read before any destination is written.
+template <typename KT>
+__global__ __launch_bounds__(256) void k_kv_compact(KvView kv0, size_t layer_stride, SeqState st) {
+  int layer = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+  const int* res = st.result + b * FIRP_RESULT_STRIDE;
+  int n = res[0], p0 = res[2];
+  const int* path = res + 3 + (st.k_cap + 1);
+  bool moved = false;
+  for (int j = 1; j < n; ++j) moved |= (path[j] != j);
+  if (!moved) return;
+  int dh = kv0.head_dim, e = threadIdx.x;
+  KT* K = (KT*)kv0.k + (size_t)b * kv0.seq_stride + (size_t)layer * layer_stride + (size_t)h * kv0.slots * dh;
+  KT* Vt = (KT*)kv0.v + (size_t)b * kv0.seq_stride + (size_t)layer * layer_stride + (size_t)h * dh * kv0.slots;
+  KT kk[FIRP_MAX_COMMIT], vv[FIRP_MAX_COMMIT];
+  if (e < dh) {
+#pragma unroll
+    for (int j = 1; j < FIRP_MAX_COMMIT; ++j)
+      if (j < n) {
+        kk[j] = K[(size_t)(p0 + path[j]) * dh + e];
+        vv[j] = Vt[(size_t)e * kv0.slots + p0 + path[j]];
+      }
+  }
+  __syncthreads();
+  if (e < dh) {
+#pragma unroll
+    for (int j = 1; j < FIRP_MAX_COMMIT; ++j)
+      if (j < n) {
+        K[(size_t)(p0 + j) * dh + e] = kk[j];
+        Vt[(size_t)e * kv0.slots + p0 + j] = vv[j];
+      }
+  }
+}
+
+void launch_kv_compact(const KvView& kv0, size_t layer_stride, int n_layers, int B, const SeqState& st,
+                       int dtype, hipStream_t s) {
+  dim3 g(n_layers, kv0.n_kv_heads, B), blk(256);
+  if (dtype == DT_BF16)
+    hipLaunchKernelGGL(k_kv_compact<bf16>, g, blk, 0, s, kv0, layer_stride, st);
+  else
+    hipLaunchKernelGGL(k_kv_compact<float>, g, blk, 0, s, kv0, layer_stride, st);
+}
+
+// ------------------------------------------------------------------------------------------
+__global__ void k_advance_by(int* p0, int seq, int n) { p0[seq] += n; }
+void launch_advance_by(int* p0, int seq, int n, hipStream_t s) {
+  hipLaunchKernelGGL(k_advance_by, dim3(1), dim3(1), 0, s, p0, seq, n);
+}
+
+__global__ void k_set_root(SeqState st, int seq, int token, int p0) {
+  st.root_tok[seq] = token;
+  st.drafts_valid[seq] = 0;
+  st.p0[seq] = p0;
+}
+void launch_set_root(const SeqState& st, int seq, int token, int p0, hipStream_t s) {
+  hipLaunchKernelGGL(k_set_root, dim3(1), dim3(1), 0, s, st, seq, token, p0);
+}
+
+// ------------------------------------------------------------------------------------------
+// helpers of the standalone projection entry
+__global__ void k_split_act(const float* __restrict__ x, int ld, Act out) {
+  int r = blockIdx.x;
+  for (int i = threadIdx.x; i < ld; i += blockDim.x) act_store<true>(out, (size_t)r * out.ld + i, x[(size_t)r * ld + i]);
+}
+void launch_split_act(const float* x, int rows, int ld, const Act& out, hipStream_t s) {
+  hipLaunchKernelGGL(k_split_act, dim3(rows), dim3(256), 0, s, x, ld, out);
+}
+
+__global__ void k_reduce_partials(Partial p, float* y) {
+  int r = blockIdx.y;
+  int c = blockIdx.x * blockDim.x + threadIdx.x;
+  if (c < p.ld) y[(size_t)r * p.ld + c] = partial_sum(p, (size_t)r * p.ld + c);
+}
+void launch_reduce_partials(const Partial& p, float* y, int rows, hipStream_t s) {
+  hipLaunchKernelGGL(k_reduce_partials, dim3((p.ld + 255) / 256, rows), dim3(256), 0, s, p, y);
+}
+
+}  // namespace firp

@@ -283,3 +283,5 @@ def workload_tree(config_name: str, anchors: str = "root") -> Tree:
     if config_name == "7b":
         return full_tree((4, 3, 2), anchors)
     return budget_tree((8, 4, 2), 63, anchors)
+
+FIRP_MAX_DEPTH = 8   # deepest tree level the library accepts

@@ -1,0 +1,51 @@
+"""Whole-step parity of the HIP library against the CPU oracle, through the C ABI."""
+import pytest
+import torch
+
+from paper_2410_20488_amd import synth
+from tests.gpu_common import compare_cache, run_lockstep
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def dev():
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    return torch.device("cuda:0")
+
+
+def test_config1_tiny_fp32_chain_32_steps(dev, progress):
+    """The small benchmark configuration: fp32, chain tree, 32 steps, exact tokens."""
+    cfg = synth.CONFIGS["tiny"]
+    w = synth.make_weights(cfg, dev)
+    rep, eng, orc = run_lockstep(cfg, w, synth.workload_tree("tiny"), prompt_len=64, n_steps=32, tol=1e-4,
+                                 progress=progress)
+    assert rep.steps == 32 and rep.tokens >= 32 and rep.tie_ambiguous == 0
+    assert max(i for i, c in enumerate(rep.accepted_hist) if c) >= 3      # injection reached depth >= 2
+    compare_cache(eng, orc, cfg, 1e-4)
+
+
+@pytest.mark.parametrize("anchors", ["root", "all"])
+def test_tiny_fp32_branching_tree_with_bias(dev, progress, anchors):
+    cfg = synth.CONFIGS["tiny"]
+    w = synth.make_weights(cfg, dev, with_bias=True)
+    tree = synth.full_tree((3, 2, 2), anchors)
+    rep, eng, orc = run_lockstep(cfg, w, tree, prompt_len=37, n_steps=9, tol=1e-4, progress=progress)
+    assert rep.tie_ambiguous == 0
+    compare_cache(eng, orc, cfg, 1e-4)
+
+
+def test_tiny_bf16_plain_kernels(dev, progress):
+    cfg = synth.CONFIGS["tiny_bf16"]
+    w = synth.make_weights(cfg, dev)
+    rep, eng, orc = run_lockstep(cfg, w, synth.full_tree((3, 2), "root"), prompt_len=70, n_steps=9, tol=2e-2,
+                                 gemm=0, progress=progress)
+    compare_cache(eng, orc, cfg, 2e-2)
+
+
+def test_tiny_gqa_random_tree(dev, progress):
+    cfg = synth.CONFIGS["tiny_gqa"]
+    w = synth.make_weights(cfg, dev, with_bias=True)
+    tree = synth.random_tree(11, 13, 2, 4, 0.4)
+    tree = synth.Tree(tree.parent, tree.rank, (1,) + tree.anchor[1:])
+    run_lockstep(cfg, w, tree, prompt_len=150, n_steps=9, tol=2e-2, gemm=0, progress=progress)
