@@ -523,8 +523,8 @@ firp_status firp_init(firp_ctx** out, const firp_model_desc* desc, const firp_we
     c->pw.assign(proj_w, proj_w + k);
     if (proj_b) c->pb.assign(proj_b, proj_b + k);
   }
-  c->gemm_kind = 0;
-  c->split = false;
+  c->gemm_kind = desc->dtype == FIRP_BF16 ? 1 : 0;  // bf16 models stream weights through MFMA
+  c->split = c->gemm_kind == 1;
   c->p0.assign(desc->max_batch, 0);
   c->drafts_valid.assign(desc->max_batch, 0);
   size_t res_bytes = (size_t)desc->max_batch * FIRP_RESULT_STRIDE * sizeof(int);

@@ -156,9 +156,20 @@ def run_lockstep(cfg, weights_gpu, tree: synth.Tree, *, prompt_len: int, n_steps
     return rep, eng, orc
 
 
-def compare_cache(eng, orc, cfg, atol):
+def compare_cache(eng, orc, cfg, atol=1e-4):
+    """Committed K/V of the library against the oracle's.  fp32 caches agree to `atol`; a bf16
+    cache holds values both sides rounded to bf16 from slightly different fp32 inputs (the same
+    2e-2-of-a-standard-deviation budget as the logits), so an entry may in addition land on the
+    neighbouring bf16 value (one unit in the last place, 2^-7 relative at most); the bulk must
+    be identical."""
     for layer in range(cfg.n_layers):
         k, v = eng.read_cache(0, layer)
         assert k.shape[0] == orc.p0
-        assert np.abs(k - orc.K[layer].float().numpy()).max() <= atol, f"K cache layer {layer}"
-        assert np.abs(v - orc.V[layer].float().numpy()).max() <= atol, f"V cache layer {layer}"
+        for name, got, ref in (("K", k, orc.K[layer].float().numpy()), ("V", v, orc.V[layer].float().numpy())):
+            diff = np.abs(got - ref)
+            if cfg.dtype == "f32":
+                assert diff.max() <= atol, f"{name} cache layer {layer}"
+            else:
+                ulp = np.exp2(np.floor(np.log2(np.maximum(np.abs(ref), 1e-30))) - 7)
+                assert (diff <= 1.001 * ulp + 2e-2 * ref.std()).all(), f"{name} cache layer {layer}: beyond tolerance"
+                assert (diff == 0).mean() > 0.5, f"{name} cache layer {layer}: {(diff == 0).mean():.3f} identical"

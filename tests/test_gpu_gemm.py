@@ -1,0 +1,41 @@
+"""Per-kernel parity of the projection kernels against the plain definition y = x W^T
+computed on the CPU in fp64 (the oracle's matmul sub-step), through the C ABI."""
+import pytest
+import torch
+
+from paper_2410_20488_amd import binding, synth
+
+pytestmark = pytest.mark.gpu
+
+SHAPES = [  # rows, n, K
+    (7, 688, 256), (7, 256, 688), (5, 520, 256), (5, 256, 352), (1, 1024, 256),
+    (4, 5120, 5120), (16, 5120, 5120), (17, 4096, 4096), (41, 4096, 11008), (44, 11008, 4096),
+    (64, 5120, 5120), (67, 5120, 5120), (67, 13824, 5120), (67, 5120, 13824), (67, 32000, 5120),
+    (80, 1024, 8192), (128, 5120, 5120), (129, 1280, 5120), (200, 5120, 1024), (256, 2048, 5120),
+]
+
+
+def _inputs(rows, n, K, dtype):
+    dev = torch.device("cuda:0")
+    x = synth.normal_tensor(7, 900 + rows, (rows, K), 1.0, torch.float32, dev)
+    w = synth.normal_tensor(7, 901 + n % 97, (n, K), 0.02, dtype, dev)
+    return x, w
+
+
+@pytest.mark.parametrize("rows,n,K", SHAPES)
+def test_mfma_projection_matches_fp64_matmul(rows, n, K):
+    x, w = _inputs(rows, n, K, torch.bfloat16)
+    y = binding.debug_gemm(x, w, kind=1).cpu().double()
+    ref = x.cpu().double() @ w.cpu().double().T
+    err = float((y - ref).abs().max() / ref.std())
+    # two bf16 planes carry 16 mantissa bits of x: rounding error per product <= 2^-17 |x||w|
+    assert err < 2e-4, err
+
+
+@pytest.mark.parametrize("rows,n,K,dtype", [(7, 688, 256, torch.float32), (67, 1024, 688, torch.float32),
+                                            (130, 520, 352, torch.bfloat16), (3, 1000, 100, torch.float32)])
+def test_plain_projection_matches_fp64_matmul(rows, n, K, dtype):
+    x, w = _inputs(rows, n, K, dtype)
+    y = binding.debug_gemm(x, w, kind=0).cpu().double()
+    ref = x.cpu().double() @ w.cpu().double().T
+    assert float((y - ref).abs().max() / ref.std()) < 2e-5
