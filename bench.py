@@ -1,0 +1,162 @@
+#!/usr/bin/env python3
+"""Benchmark of the FIRP decoding step on one MI355X.
+
+A "step" is one firp_step: the whole hot path (candidate fill, embedding, all decoder layers
+with tree attention, the FIRP map, lm-head, greedy verification, draft selection, KV commit)
+over one synthetic batch.  Default workload: the LLaMA-2-13B-shaped bf16 model, k = 3, prompt of
+1024 uniform-random tokens, the 64-node draft tree, anchors = {root}.  Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E bandwidth
+
+
+def algorithmic_bytes(cfg, n_nodes: int, t_hi: int, ctx: int) -> float:
+    """Bytes the method must move in one step: every weight once, the live KV cache once, the
+    step rows' K/V once out and once in (bf16 = 2 bytes)."""
+    e = 2 if cfg.dtype == "bf16" else 4
+    kv_row = 2 * cfg.n_kv_heads * cfg.head_dim * e                 # K and V of one row, one layer
+    weights = e * (cfg.n_layers * cfg.layer_params() + cfg.vocab * cfg.d_model + cfg.k * cfg.d_model ** 2)
+    kv_sweep = ctx * kv_row * cfg.n_layers
+    step_rows = 2 * kv_row * (n_nodes * cfg.firp_layer + t_hi * (cfg.n_layers - cfg.firp_layer))
+    return float(weights + kv_sweep + step_rows)
+
+
+def cpu_baseline(cfg, weights_gpu, tree, prompt, budget_note: str):
+    """Time the CPU oracle, as it stands, on a bounded sample of the same workload: the same
+    widths, prompt and tree with only the first 2 and the first 4 of the layers; the per-layer
+    cost from the difference is extrapolated to the full depth."""
+    import torch
+    from paper_2410_20488_amd import synth
+    from tests.helpers import make_oracle
+
+    def sample(n_layers):
+        sub = synth.scaled_config(cfg, n_layers, n_layers // 2)
+        w = {}
+        for k, v in weights_gpu.items():
+            if v is None:
+                w[k] = None
+            elif isinstance(v, list):
+                keep = v if k.startswith("proj") else v[:n_layers]
+                w[k] = [t.cpu() for t in keep]
+            else:
+                w[k] = v.cpu()
+        o = make_oracle(sub, w)
+        o.prefill(prompt)
+        args = dict(parent=list(tree.parent), rank=list(tree.rank), anchor=list(tree.anchor))
+        t0 = time.perf_counter()
+        o.step(**args)
+        return time.perf_counter() - t0
+
+    t2 = sample(2)
+    t4 = sample(4)
+    per_layer = max((t4 - t2) / 2.0, 0.0)
+    full = t2 + per_layer * (cfg.n_layers - 2)
+    return {"value": round(full * 1e3, 1), "unit": "ms/step", "cores": torch.get_num_threads(), "kind": "oracle",
+            "sample": f"fp32 oracle step at the full widths, prompt and tree with 2 and with 4 of the "
+                      f"{cfg.n_layers} layers ({t2:.2f} s, {t4:.2f} s); per-layer cost extrapolated to full depth"
+                      + budget_note}
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=64)
+    ap.add_argument("--warmup", type=int, default=8)
+    ap.add_argument("--config", default="13b", choices=["13b", "7b", "tiny_bf16"])
+    ap.add_argument("--prompt", type=int, default=0, help="prompt length (default: the configuration's)")
+    ap.add_argument("--anchors", default="root", choices=["root", "all"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (the step is a single-GPU kernel path); "
+              "use --gpus 1", file=sys.stderr)
+        return 2
+
+    import torch
+    from paper_2410_20488_amd import synth
+    from tests.gpu_common import make_engine
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    dev = torch.device("cuda:0")
+    cfg = synth.CONFIGS[args.config]
+    tree = synth.workload_tree(args.config, args.anchors)
+    prompt_len = args.prompt or {"13b": 1024, "7b": 512, "tiny_bf16": 64}[args.config]
+    t_start = time.time()
+    weights = synth.make_weights(cfg, dev)
+    torch.cuda.synchronize()
+    n_anchor = sum(tree.anchor)
+    t_hi = tree.n_nodes + cfg.k * n_anchor
+    total_steps = args.warmup + args.steps + 16
+    eng = make_engine(cfg, weights, max_ctx=prompt_len + (cfg.k + 1) * (total_steps + 2) + 8,
+                      max_nodes=tree.n_nodes, max_rows=max(128, t_hi), b_max=8)
+    prompt = synth.prompt_tokens(cfg.seed, prompt_len, cfg.vocab).tolist()
+    eng.prefill([prompt])
+    setup_s = time.time() - t_start
+    targs = (list(tree.parent), list(tree.rank), list(tree.anchor))
+    for _ in range(args.warmup):
+        eng.step(*targs)
+    ctx_first = eng.ctx_len()[0]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    tokens = 0
+    for _ in range(args.steps):
+        tokens += len(eng.step(*targs)[0])
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ctx_last = eng.ctx_len()[0]
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+
+    # roofline of the dominant kernel (the weight-streaming projection): HIP events on the
+    # library's stream around every launch, over 16 further steps
+    eng.set_option("time_gemm", 1)
+    for _ in range(16):
+        eng.step(*targs)
+    launches, gemm_ms, gemm_bytes = eng.gemm_timing()
+    eng.set_option("time_gemm", 0)
+    gemm_gbs = gemm_bytes / (gemm_ms * 1e-3) / 1e9 if gemm_ms > 0 else 0.0
+
+    step_bytes = algorithmic_bytes(cfg, tree.n_nodes, t_hi, (ctx_first + ctx_last) // 2)
+    step_gbs = step_bytes / (ms_per_step * 1e-3) / 1e9
+    out = {
+        "metric": "firp_step latency (ms) and achieved HBM GB/s vs peak, 13B-shape bf16, k=3",
+        "value": round(ms_per_step, 4), "unit": "ms/step", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": False,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"LLaMA-2-{args.config.upper()}-shaped decoder, bf16 random-init, k={cfg.k} maps at "
+                               f"layer {cfg.firp_layer}, batch 1, prompt {prompt_len} uniform-random tokens, "
+                               f"{tree.n_nodes}-node draft tree, anchors={args.anchors} (T_hi={t_hi}), "
+                               f"ctx {ctx_first}->{ctx_last}"},
+        "step_algorithmic_GB": round(step_bytes / 1e9, 3),
+        "step_achieved_GBps": round(step_gbs, 1),
+        "step_frac_of_hbm_peak": round(step_gbs / HBM_PEAK_GBS, 4),
+        "tokens_per_step": round(tokens / args.steps, 3),
+        "setup_s": round(setup_s, 1),
+        "roofline": {"bound": "hbm", "kernel": "k_gemm_mfma", "achieved": round(gemm_gbs, 1), "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": round(gemm_gbs / HBM_PEAK_GBS, 4), "traffic": None,
+                     "launches_timed": launches,
+                     "avg_launch_us": round(gemm_ms * 1e3 / max(launches, 1), 2),
+                     "algorithmic_MB_per_launch": round(gemm_bytes / max(launches, 1) / 1e6, 2),
+                     "share_of_step_time": round(gemm_ms / 16 / ms_per_step, 3)},
+    }
+    if not args.no_cpu_baseline:
+        del eng
+        out["cpu_baseline"] = cpu_baseline(cfg, weights, tree, prompt, "")
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

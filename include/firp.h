@@ -170,9 +170,15 @@ firp_status firp_debug_read_cache(firp_ctx *ctx, int32_t seq, int32_t layer, flo
                                   float *v_out);
 
 /* Behaviour switches for tests and measurements.  name = "gemm" value 0 (plain tiled kernel)
- * or 1 (MFMA weight-streaming kernel, bf16 models only); "graph" 0/1 (replay the step from
- * a captured HIP graph).  Returns FIRP_EINVAL for an unknown name or value. */
+ * or 1 (MFMA weight-streaming kernel, bf16 models only; the default for them); "time_gemm" 0/1
+ * (see firp_get_gemm_timing).  Returns FIRP_EINVAL for an unknown name or value. */
 firp_status firp_set_option(firp_ctx *ctx, const char *name, int32_t value);
+
+/* With option "time_gemm" = 1 every launch of the MFMA projection kernel inside firp_step is
+ * bracketed by HIP events on the library's stream; this returns the totals since the option
+ * was set: kernel launches, their summed duration, and the weight bytes they streamed. */
+firp_status firp_get_gemm_timing(const firp_ctx *ctx, int64_t *launches, double *total_ms,
+                                 double *weight_bytes);
 
 /* Standalone entry to the projection kernel for per-kernel parity and bandwidth tests:
  * y[R, n] (DEVICE fp32) = x[R, K] (DEVICE fp32) . w[n, K]^T (DEVICE, `dtype`), on `hip_stream`,

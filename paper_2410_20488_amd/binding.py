@@ -76,6 +76,7 @@ def load_library() -> C.CDLL:
         "firp_get_ctx_len": (C.c_int, [vp, i32p]),
         "firp_debug_read_cache": (C.c_int, [vp, C.c_int32, C.c_int32, C.POINTER(C.c_float), C.POINTER(C.c_float)]),
         "firp_set_option": (C.c_int, [vp, C.c_char_p, C.c_int32]),
+        "firp_get_gemm_timing": (C.c_int, [vp, C.POINTER(C.c_int64), C.POINTER(C.c_double), C.POINTER(C.c_double)]),
         "firp_gemm_workspace_bytes": (C.c_size_t, [C.c_int32, C.c_int32, C.c_int32]),
         "firp_debug_gemm": (C.c_int, [vp, vp, vp, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32, vp,
                                        C.c_size_t, vp]),
@@ -89,7 +90,7 @@ def load_library() -> C.CDLL:
 
 EXPORTED = ["firp_workspace_bytes", "firp_init", "firp_prefill", "firp_step", "firp_reset", "firp_destroy",
             "firp_last_error", "firp_step_with_candidates", "firp_check_tree", "firp_debug_last_logits", "firp_debug_last_path",
-            "firp_get_drafts", "firp_get_ctx_len", "firp_debug_read_cache", "firp_set_option",
+            "firp_get_drafts", "firp_get_ctx_len", "firp_debug_read_cache", "firp_set_option", "firp_get_gemm_timing",
             "firp_gemm_workspace_bytes", "firp_debug_gemm"]
 
 
@@ -246,6 +247,12 @@ class Engine:
         n = np.zeros(self.batch, dtype=np.int32)
         self._check(self.lib.firp_get_ctx_len(self.ctx, _p(n)))
         return n.tolist()
+
+    def gemm_timing(self):
+        """(launches, total ms, weight bytes) of the timed projection launches."""
+        n, ms, by = C.c_int64(0), C.c_double(0), C.c_double(0)
+        self._check(self.lib.firp_get_gemm_timing(self.ctx, C.byref(n), C.byref(ms), C.byref(by)))
+        return n.value, ms.value, by.value
 
     def read_cache(self, seq: int, layer: int):
         n = self.ctx_len()[seq]

@@ -55,6 +55,25 @@ __device__ __forceinline__ void act_store(const Act& a, size_t idx, float v) {
   }
 }
 
+// four consecutive activations (idx % 4 == 0): one 8-byte store per plane
+template <bool SPLIT>
+__device__ __forceinline__ void act_store4(const Act& a, size_t idx, float v0, float v1, float v2, float v3) {
+  if constexpr (SPLIT) {
+    bf16 h0 = f32_to_bf16(v0), h1 = f32_to_bf16(v1), h2 = f32_to_bf16(v2), h3 = f32_to_bf16(v3);
+    bf16 l0 = f32_to_bf16(v0 - to_f32(h0)), l1 = f32_to_bf16(v1 - to_f32(h1));
+    bf16 l2 = f32_to_bf16(v2 - to_f32(h2)), l3 = f32_to_bf16(v3 - to_f32(h3));
+    uint2 ph, pl;
+    ph.x = (unsigned)h0.v | ((unsigned)h1.v << 16);
+    ph.y = (unsigned)h2.v | ((unsigned)h3.v << 16);
+    pl.x = (unsigned)l0.v | ((unsigned)l1.v << 16);
+    pl.y = (unsigned)l2.v | ((unsigned)l3.v << 16);
+    *(uint2*)(a.hi + idx) = ph;
+    *(uint2*)(a.lo + idx) = pl;
+  } else {
+    *(float4*)(a.f32 + idx) = make_float4(v0, v1, v2, v3);
+  }
+}
+
 // ---- split-K partial sums ------------------------------------------------------------------
 // A projection leaves S partial products [S][rows][n] (fp32); its consumer adds them up.
 struct Partial {

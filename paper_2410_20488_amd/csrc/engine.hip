@@ -48,6 +48,9 @@ struct firp_ctx {
   int k = 0, l = 0, dtype = 0;
   bool split = false;   // activations as hi/lo bf16 planes (MFMA projection)
   int gemm_kind = 0;    // 0 plain, 1 MFMA
+  int attn_kind = 0;    // 0 plain, 1 MFMA flash-decode (needs the bf16 planes of q)
+  bool cache_clean = false;  // the KV cache holds only finite values (zero-filled once)
+  float* attn_scratch = nullptr;
   hipStream_t stream = nullptr;
   // weights
   const void* embed = nullptr;
@@ -77,6 +80,12 @@ struct firp_ctx {
   HostTree cur;          // topology whose tables are on the device
   bool tables_valid = false;
   int last_rows = 0, last_N = 0, last_P = 0;
+  // optional timing of the projection launches (HIP events on the library's stream)
+  bool time_gemm = false;
+  std::vector<hipEvent_t> ev;
+  size_t ev_used = 0;
+  double gemm_ms = 0.0, gemm_bytes = 0.0;
+  long gemm_launches = 0;
   int* h_result = nullptr;  // pinned when a device is present
   bool h_result_pinned = true;
   std::string err;
@@ -104,6 +113,7 @@ bool desc_ok(const firp_model_desc* d, int k, std::string& why) {
       d->d_ffn < 1 || d->vocab < 2)
     return bad("non-positive model dimension");
   if (d->head_dim % 2 || d->head_dim > 256) return bad("head_dim must be even and <= 256");
+  if (d->d_model % 4 || d->d_model > 8192 || d->d_ffn % 4) return bad("d_model must be a multiple of 4 and <= 8192, d_ffn a multiple of 4");
   if (d->n_q_heads % d->n_kv_heads) return bad("n_q_heads must be a multiple of n_kv_heads");
   if (d->dtype != FIRP_F32 && d->dtype != FIRP_BF16) return bad("unknown dtype");
   if (!(d->rms_eps > 0.f) || !(d->rope_base > 1.f)) return bad("rms_eps / rope_base out of range");
@@ -124,6 +134,7 @@ size_t carve(firp_ctx* c, char* base) {
   c->x = cv.take<float>((size_t)Rp * d.d_model);
   c->part = cv.take<float>(c->part_elems);
   c->logits = cv.take<float>((size_t)Rp * d.vocab);
+  c->attn_scratch = cv.take<float>(attention_mfma_scratch_floats(Rp, d.n_q_heads, d.head_dim));
   auto act = [&](Act& a, int ld) {
     a.ld = ld;
     a.f32 = cv.take<float>((size_t)Rp * ld);
@@ -214,7 +225,14 @@ Partial project(firp_ctx* c, const Act& in, const void* w, int rows, int n, int 
   out.p = c->part;
   if (c->gemm_kind == 1 && gemm_mfma_supported(rows, n, K)) {
     GemmPlan plan = gemm_mfma_plan(rows, n, K, like ? like->S : 0);
+    bool timed = c->time_gemm && c->ev_used + 2 <= c->ev.size();
+    if (timed) (void)hipEventRecord(c->ev[c->ev_used++], c->stream);
     launch_gemm_mfma(in, (const bf16*)w, c->part + col, ld, out.stride, rows, n, K, plan, c->stream);
+    if (timed) {
+      (void)hipEventRecord(c->ev[c->ev_used++], c->stream);
+      c->gemm_bytes += 2.0 * (double)n * (double)K;
+      c->gemm_launches += (rows + 127) / 128;
+    }
     out.S = plan.S;
   } else {
     launch_gemm_simple(in.f32, in.ld, w, c->dtype, c->part + col, ld, rows, n, K, c->stream);
@@ -225,7 +243,7 @@ Partial project(firp_ctx* c, const Act& in, const void* w, int rows, int n, int 
 
 // The decoder over `rows_lo` rows for layers < l and `rows_hi` rows from layer l on.  With
 // `head`, ends with final norm, lm-head and argmax / top-b.
-firp_status forward(firp_ctx* c, int rows_lo, int rows_hi, int n_anchor_rows, int n_local_lo,
+firp_status forward(firp_ctx* c, int B, int rows_lo, int rows_hi, int n_anchor_rows, int n_local_lo,
                     int n_local_hi, int real_rows, bool head, int max_ctx_now) {
   const firp_model_desc& d = c->d;
   hipStream_t s = c->stream;
@@ -270,8 +288,12 @@ firp_status forward(firp_ctx* c, int rows_lo, int rows_hi, int n_anchor_rows, in
     project(c, c->act_d, c->wv[layer], rows, kvd, d.d_model, c->qkv_ld, qd + kvd, &q);
     KvView kv = kv_view(c, layer);
     launch_rope_kv(q, rows, d.n_q_heads, rt, c->st.p0, d.rope_base, c->act_q, sp, kv, c->dtype, s);
-    launch_attention_simple(c->act_q, sp, rows, d.n_q_heads, rt, c->st.p0, kv, c->dtype, c->act_o, n_local,
-                            max_ctx_now + n_local, s);
+    if (c->attn_kind == 1 && sp)
+      launch_attention_mfma(c->act_q, rows, d.n_q_heads, B, n_local_lo, n_local - n_local_lo, rt, c->st.p0,
+                            max_ctx_now, kv, c->attn_scratch, c->act_o, s);
+    else
+      launch_attention_simple(c->act_q, sp, rows, d.n_q_heads, rt, c->st.p0, kv, c->dtype, c->act_o, n_local,
+                              max_ctx_now + n_local, s);
     Partial o = project(c, c->act_o, c->wo[layer], rows, d.d_model, qd, d.d_model, 0, nullptr);
     launch_add_rmsnorm(c->x, o, rows, d.d_model, c->n2[layer], c->dtype, d.rms_eps, c->act_d, sp, s);
     Partial g = project(c, c->act_d, c->wg[layer], rows, d.d_ffn, d.d_model, 2 * d.d_ffn, 0, nullptr);
@@ -426,7 +448,7 @@ firp_status run_step(firp_ctx* c, const firp_tree* tree, const int32_t* node_tok
       return c->fail(FIRP_ECAPACITY, "sequence %d: %d cached + %d new tokens exceed max_ctx %d", b, c->p0[b], max_depth + 1, c->d.max_ctx);
     ctx_max = std::max(ctx_max, c->p0[b]);
   }
-  if ((size_t)(c->d.head_dim + ctx_max + T) * sizeof(float) > 64 * 1024)
+  if (!(c->attn_kind == 1 && c->split) && (size_t)(c->d.head_dim + ctx_max + T) * sizeof(float) > 64 * 1024)
     return c->fail(FIRP_ECAPACITY, "context of %d tokens exceeds the plain attention kernel's limit", ctx_max);
   st = upload_tree(c, B, parent, rank, anchor);
   if (st != FIRP_OK) return st;
@@ -438,12 +460,17 @@ firp_status run_step(firp_ctx* c, const firp_tree* tree, const int32_t* node_tok
     inj = c->injected;
   }
   launch_fill_tokens(c->st, tree_tab(c, N, P), B, inj, s);
-  st = forward(c, B * N, B * T, B * n_anchor, N, T, B * N, true, ctx_max);
+  st = forward(c, B, B * N, B * T, B * n_anchor, N, T, B * N, true, ctx_max);
   if (st != FIRP_OK) return st;
   launch_verify_select(c->st, tree_tab(c, N, P), B, s);
   launch_kv_compact(kv_view(c, 0), c->kv_layer_stride, c->d.n_layers, B, c->st, c->dtype, s);
   HIPCHK(hipMemcpyAsync(c->h_result, c->st.result, (size_t)B * FIRP_RESULT_STRIDE * sizeof(int), hipMemcpyDeviceToHost, s));
   HIPCHK(hipStreamSynchronize(s));
+  for (size_t i = 0; i + 1 < c->ev_used; i += 2) {
+    float ms = 0.f;
+    if (hipEventElapsedTime(&ms, c->ev[i], c->ev[i + 1]) == hipSuccess) c->gemm_ms += ms;
+  }
+  c->ev_used = 0;
   for (int b = 0; b < B; ++b) {
     const int* r = c->h_result + b * FIRP_RESULT_STRIDE;
     n_accepted[b] = r[0];
@@ -525,6 +552,7 @@ firp_status firp_init(firp_ctx** out, const firp_model_desc* desc, const firp_we
   }
   c->gemm_kind = desc->dtype == FIRP_BF16 ? 1 : 0;  // bf16 models stream weights through MFMA
   c->split = c->gemm_kind == 1;
+  c->attn_kind = (c->split && attention_mfma_supported(desc->head_dim, desc->dtype)) ? 1 : 0;
   c->p0.assign(desc->max_batch, 0);
   c->drafts_valid.assign(desc->max_batch, 0);
   size_t res_bytes = (size_t)desc->max_batch * FIRP_RESULT_STRIDE * sizeof(int);
@@ -549,6 +577,7 @@ firp_status firp_reset(firp_ctx* c) {
 
 void firp_destroy(firp_ctx* c) {
   if (!c) return;
+  for (auto& e : c->ev) (void)hipEventDestroy(e);
   if (c->h_result) {
     if (c->h_result_pinned)
       (void)hipHostFree(c->h_result);
@@ -576,11 +605,18 @@ firp_status firp_prefill(firp_ctx* c, int32_t batch, const int32_t* tokens, cons
   for (size_t i = 0; i < total; ++i)
     if (tokens[i] < 0 || tokens[i] >= c->d.vocab) return c->fail(FIRP_EINVAL, "token %zu = %d outside the vocabulary", i, tokens[i]);
   int C = c->d.max_rows;
-  if ((size_t)(c->d.head_dim + longest + C) * sizeof(float) > 64 * 1024)
+  if (!(c->attn_kind == 1 && c->split) && (size_t)(c->d.head_dim + longest + C) * sizeof(float) > 64 * 1024)
     return c->fail(FIRP_ECAPACITY, "prompt of %d tokens exceeds the plain attention kernel's limit", longest);
   hipStream_t s = c->stream;
   c->prefilled = false;
   c->tables_valid = false;
+  if (!c->cache_clean) {
+    // masked keys are multiplied by a zero probability: the cache must never hold NaN or Inf
+    size_t bytes = (size_t)c->d.max_batch * c->kv_seq_stride * c->esize;
+    HIPCHK(hipMemsetAsync(c->kcache, 0, bytes, s));
+    HIPCHK(hipMemsetAsync(c->vcache, 0, bytes, s));
+    c->cache_clean = true;
+  }
   // prompt[:-1] through the decoder in chunks: a chunk is a chain whose mask is lower-triangular
   std::vector<int> seq(C), local(C), pos(C);
   std::vector<unsigned long long> mask((size_t)C * FIRP_MASK_WORDS, 0);
@@ -602,7 +638,7 @@ firp_status firp_prefill(firp_ctx* c, int32_t batch, const int32_t* tokens, cons
     while (done < todo) {
       int n = std::min(C, todo - done);
       HIPCHK(hipMemcpyAsync(c->st.tok, tk + done, n * sizeof(int), hipMemcpyHostToDevice, s));
-      firp_status st = forward(c, n, n, 0, n, n, n, false, done);
+      firp_status st = forward(c, 1, n, n, 0, n, n, n, false, done);
       if (st != FIRP_OK) return st;
       launch_advance_by(c->st.p0, b, n, s);
       HIPCHK(hipStreamSynchronize(s));  // the token staging buffer is reused by the next chunk
@@ -736,16 +772,53 @@ firp_status firp_set_option(firp_ctx* c, const char* name, int32_t value) {
     if (value == 0) {
       c->gemm_kind = 0;
       c->split = false;
+      c->attn_kind = 0;
       return FIRP_OK;
     }
     if (value == 1 && c->dtype == FIRP_BF16) {
       c->gemm_kind = 1;
       c->split = true;
+      c->attn_kind = attention_mfma_supported(c->d.head_dim, c->dtype) ? 1 : 0;
       return FIRP_OK;
     }
     return c->fail(FIRP_EINVAL, "gemm kind %d is not available for this model", value);
   }
+  if (!strcmp(name, "attn")) {
+    if (value == 0) {
+      c->attn_kind = 0;
+      return FIRP_OK;
+    }
+    if (value == 1 && c->split && attention_mfma_supported(c->d.head_dim, c->dtype)) {
+      c->attn_kind = 1;
+      return FIRP_OK;
+    }
+    return c->fail(FIRP_EINVAL, "attention kind %d is not available for this model", value);
+  }
+  if (!strcmp(name, "time_gemm")) {
+    if (value != 0 && value != 1) return c->fail(FIRP_EINVAL, "time_gemm takes 0 or 1");
+    if (value && c->ev.empty()) {
+      c->ev.resize(2 * (size_t)(8 * c->d.n_layers + 16));
+      for (auto& e : c->ev)
+        if (hipEventCreate(&e) != hipSuccess) {
+          c->ev.clear();
+          return c->fail(FIRP_EDEVICE, "hipEventCreate failed");
+        }
+    }
+    c->time_gemm = value != 0;
+    c->gemm_ms = c->gemm_bytes = 0.0;
+    c->gemm_launches = 0;
+    c->ev_used = 0;
+    return FIRP_OK;
+  }
   return c->fail(FIRP_EINVAL, "unknown option '%s'", name);
+}
+
+firp_status firp_get_gemm_timing(const firp_ctx* c, int64_t* launches, double* total_ms, double* weight_bytes) {
+  if (!c) return FIRP_EINVAL;
+  if (launches) *launches = c->gemm_launches;
+  if (total_ms) *total_ms = c->gemm_ms;
+  if (weight_bytes) *weight_bytes = c->gemm_bytes;
+  return FIRP_OK;
 }
 
 size_t firp_gemm_workspace_bytes(int32_t rows, int32_t n, int32_t k_dim) {

@@ -81,6 +81,15 @@ void launch_attention_simple(const Act& q, bool split, int rows, int n_q_heads, 
                              const int* p0, const KvView& kv, int dtype, const Act& out,
                              int n_local, int max_keys, hipStream_t s);
 
+// MFMA flash-decode attention over a bf16 cache; see attention_mfma.hip.  `scratch` holds the
+// per-split partial results (attention_mfma_scratch_floats floats).
+#define FIRP_ATTN_MAX_SPLITS 16
+bool attention_mfma_supported(int head_dim, int dtype);
+size_t attention_mfma_scratch_floats(int rows, int n_q_heads, int head_dim);
+void launch_attention_mfma(const Act& q, int rows, int n_q_heads, int B, int n_real_per_seq,
+                           int n_pseudo_per_seq, const RowTab& rt, const int* p0, int max_ctx_now,
+                           const KvView& kv, float* scratch, const Act& out, hipStream_t s);
+
 // plain tiled projection: y[S=1][rows][n] = x_f32[rows][K] . W[n][K]^T
 void launch_gemm_simple(const float* x, int ldx, const void* w, int dtype, float* y, int ldy,
                         int rows, int n, int K, hipStream_t s);

@@ -50,26 +50,55 @@ void launch_embed(const void* embed, int dtype, const int* tok, int rows, int d,
 
 // ------------------------------------------------------------------------------------------
 // Residual update + RMSNorm: x[r] += sum_s part[s][r]; act[r] = x[r] / sqrt(mean(x^2)+eps) * g.
+// One workgroup per row; the row stays in registers between the two passes (d <= 8192),
+// all loads of a thread are independent 128-bit loads.
 template <typename GT, bool SPLIT, bool NORM>
 __global__ __launch_bounds__(256) void k_add_rmsnorm(float* x, Partial part, int d,
                                                      const GT* __restrict__ gain, float eps, Act out) {
   __shared__ float red[4];
+  constexpr int MAXV = 8;  // float4 per thread
   int r = blockIdx.x;
-  float* xr = x + (size_t)r * d;
+  float4* xr = (float4*)(x + (size_t)r * d);
+  const int nv = d >> 2;
+  float4 v[MAXV];
   float ss = 0.f;
-  for (int i = threadIdx.x; i < d; i += 256) {
-    float v = xr[i];
-    if (part.p) {
-      v += partial_sum(part, (size_t)r * part.ld + i);
-      xr[i] = v;
+#pragma unroll
+  for (int e = 0; e < MAXV; ++e) {
+    int i = threadIdx.x + e * 256;
+    if (i < nv) {
+      float4 a = xr[i];
+      if (part.p) {
+        const float4* pp = (const float4*)(part.p + (size_t)r * part.ld) + i;
+        float4 q[8];
+#pragma unroll
+        for (int sp = 0; sp < 8; ++sp)
+          if (sp < part.S) q[sp] = *(const float4*)((const float*)pp + (size_t)sp * part.stride);
+#pragma unroll
+        for (int sp = 0; sp < 8; ++sp)
+          if (sp < part.S) {
+            a.x += q[sp].x;
+            a.y += q[sp].y;
+            a.z += q[sp].z;
+            a.w += q[sp].w;
+          }
+        xr[i] = a;
+      }
+      v[e] = a;
+      ss += a.x * a.x + a.y * a.y + a.z * a.z + a.w * a.w;
     }
-    ss += v * v;
   }
   if constexpr (NORM) {
     ss = block_sum_256(ss, red);
     float inv = 1.0f / sqrtf(ss / (float)d + eps);
-    for (int i = threadIdx.x; i < d; i += 256)
-      act_store<SPLIT>(out, (size_t)r * out.ld + i, xr[i] * inv * to_f32(gain[i]));
+#pragma unroll
+    for (int e = 0; e < MAXV; ++e) {
+      int i = threadIdx.x + e * 256;
+      if (i < nv) {
+        size_t o = (size_t)r * out.ld + (size_t)i * 4;
+        act_store4<SPLIT>(out, o, v[e].x * inv * to_f32(gain[i * 4 + 0]), v[e].y * inv * to_f32(gain[i * 4 + 1]),
+                          v[e].z * inv * to_f32(gain[i * 4 + 2]), v[e].w * inv * to_f32(gain[i * 4 + 3]));
+      }
+    }
   }
 }
 
@@ -151,20 +180,26 @@ void launch_rope_kv(const Partial& qkv, int rows, int n_q_heads, const RowTab& r
 
 // ------------------------------------------------------------------------------------------
 // SwiGLU: act = silu(gate) * up, gate = columns [0,F), up = columns [F,2F) of the partials.
+// Four columns per thread (F % 4 == 0).
 template <bool SPLIT>
 __global__ void k_swiglu(Partial gu, int F, Act out) {
   int r = blockIdx.y;
-  int j = blockIdx.x * blockDim.x + threadIdx.x;
+  int j = (blockIdx.x * blockDim.x + threadIdx.x) * 4;
   if (j >= F) return;
-  float g = partial_sum(gu, (size_t)r * gu.ld + j);
-  float u = partial_sum(gu, (size_t)r * gu.ld + F + j);
-  float sg = g / (1.0f + expf(-g));
-  act_store<SPLIT>(out, (size_t)r * out.ld + j, sg * u);
+  const float* pg = gu.p + (size_t)r * gu.ld + j;
+  float4 g = *(const float4*)pg, u = *(const float4*)(pg + F);
+  for (int sp = 1; sp < gu.S; ++sp) {
+    float4 a = *(const float4*)(pg + (size_t)sp * gu.stride), b = *(const float4*)(pg + F + (size_t)sp * gu.stride);
+    g.x += a.x; g.y += a.y; g.z += a.z; g.w += a.w;
+    u.x += b.x; u.y += b.y; u.z += b.z; u.w += b.w;
+  }
+  act_store4<SPLIT>(out, (size_t)r * out.ld + j, g.x / (1.0f + expf(-g.x)) * u.x, g.y / (1.0f + expf(-g.y)) * u.y,
+                    g.z / (1.0f + expf(-g.z)) * u.z, g.w / (1.0f + expf(-g.w)) * u.w);
 }
 
 void launch_swiglu(const Partial& gate_up, int rows, int d_ffn, const Act& out, bool split,
                    hipStream_t s) {
-  dim3 g((d_ffn + 255) / 256, rows), b(256);
+  dim3 g((d_ffn / 4 + 255) / 256, rows), b(256);
   if (split)
     hipLaunchKernelGGL(k_swiglu<true>, g, b, 0, s, gate_up, d_ffn, out);
   else
