@@ -225,9 +225,11 @@ Partial project(firp_ctx* c, const Act& in, const void* w, int rows, int n, int 
   out.p = c->part;
   if (c->gemm_kind == 1 && gemm_mfma_supported(rows, n, K)) {
     GemmPlan plan = gemm_mfma_plan(rows, n, K, like ? like->S : 0);
+    if ((size_t)plan.S * out.stride > c->part_elems)  // never outgrow the partial-sum buffer
+      plan = gemm_mfma_plan(rows, n, K, (int)std::max<size_t>(1, c->part_elems / out.stride));
     bool timed = c->time_gemm && c->ev_used + 2 <= c->ev.size();
     if (timed) (void)hipEventRecord(c->ev[c->ev_used++], c->stream);
-    launch_gemm_mfma(in, (const bf16*)w, c->part + col, ld, out.stride, rows, n, K, plan, c->stream);
+    launch_gemm_mfma(in, wseg1(w, n), c->part + col, ld, out.stride, rows, n, K, plan, c->stream);
     if (timed) {
       (void)hipEventRecord(c->ev[c->ev_used++], c->stream);
       c->gemm_bytes += 2.0 * (double)n * (double)K;
@@ -239,6 +241,37 @@ Partial project(firp_ctx* c, const Act& in, const void* w, int rows, int n, int 
     out.S = 1;
   }
   return out;
+}
+
+// Up to three matrices sharing the input, written side by side (q|k|v, gate|up): one launch of
+// the MFMA kernel, or one plain launch per matrix.
+Partial project_stacked(firp_ctx* c, const Act& in, const void* w0, int n0, const void* w1, int n1,
+                        const void* w2, int n2, int rows, int K) {
+  int n = n0 + n1 + n2;
+  if (c->gemm_kind == 1 && gemm_mfma_supported(rows, n, K) && n0 % 4 == 0 && n1 % 4 == 0) {
+    Partial out;
+    out.ld = n;
+    out.stride = (size_t)c->Rpad * n;
+    out.p = c->part;
+    GemmPlan plan = gemm_mfma_plan(rows, n, K, 0);
+    if ((size_t)plan.S * out.stride > c->part_elems)
+      plan = gemm_mfma_plan(rows, n, K, (int)std::max<size_t>(1, c->part_elems / out.stride));
+    bool timed = c->time_gemm && c->ev_used + 2 <= c->ev.size();
+    if (timed) (void)hipEventRecord(c->ev[c->ev_used++], c->stream);
+    WSeg ws{(const bf16*)w0, (const bf16*)w1, (const bf16*)w2, n0, n1};
+    launch_gemm_mfma(in, ws, c->part, n, out.stride, rows, n, K, plan, c->stream);
+    if (timed) {
+      (void)hipEventRecord(c->ev[c->ev_used++], c->stream);
+      c->gemm_bytes += 2.0 * (double)n * (double)K;
+      c->gemm_launches += (rows + 127) / 128;
+    }
+    out.S = plan.S;
+    return out;
+  }
+  Partial q = project(c, in, w0, rows, n0, K, n, 0, nullptr);
+  project(c, in, w1, rows, n1, K, n, n0, &q);
+  if (n2 > 0) project(c, in, w2, rows, n2, K, n, n0 + n1, &q);
+  return q;
 }
 
 // The decoder over `rows_lo` rows for layers < l and `rows_hi` rows from layer l on.  With
@@ -283,9 +316,7 @@ firp_status forward(firp_ctx* c, int B, int rows_lo, int rows_hi, int n_anchor_r
       pending = Partial{};
     }
     launch_add_rmsnorm(c->x, pending, rows, d.d_model, c->n1[layer], c->dtype, d.rms_eps, c->act_d, sp, s);
-    Partial q = project(c, c->act_d, c->wq[layer], rows, qd, d.d_model, c->qkv_ld, 0, nullptr);
-    project(c, c->act_d, c->wk[layer], rows, kvd, d.d_model, c->qkv_ld, qd, &q);
-    project(c, c->act_d, c->wv[layer], rows, kvd, d.d_model, c->qkv_ld, qd + kvd, &q);
+    Partial q = project_stacked(c, c->act_d, c->wq[layer], qd, c->wk[layer], kvd, c->wv[layer], kvd, rows, d.d_model);
     KvView kv = kv_view(c, layer);
     launch_rope_kv(q, rows, d.n_q_heads, rt, c->st.p0, d.rope_base, c->act_q, sp, kv, c->dtype, s);
     if (c->attn_kind == 1 && sp)
@@ -296,8 +327,7 @@ firp_status forward(firp_ctx* c, int B, int rows_lo, int rows_hi, int n_anchor_r
                               max_ctx_now + n_local, s);
     Partial o = project(c, c->act_o, c->wo[layer], rows, d.d_model, qd, d.d_model, 0, nullptr);
     launch_add_rmsnorm(c->x, o, rows, d.d_model, c->n2[layer], c->dtype, d.rms_eps, c->act_d, sp, s);
-    Partial g = project(c, c->act_d, c->wg[layer], rows, d.d_ffn, d.d_model, 2 * d.d_ffn, 0, nullptr);
-    project(c, c->act_d, c->wu[layer], rows, d.d_ffn, d.d_model, 2 * d.d_ffn, d.d_ffn, &g);
+    Partial g = project_stacked(c, c->act_d, c->wg[layer], d.d_ffn, c->wu[layer], d.d_ffn, nullptr, 0, rows, d.d_model);
     launch_swiglu(g, rows, d.d_ffn, c->act_f, sp, s);
     pending = project(c, c->act_f, c->wd[layer], rows, d.d_model, d.d_ffn, d.d_model, 0, nullptr);
     pending_rows = rows;
@@ -847,7 +877,7 @@ firp_status firp_debug_gemm(const float* x, const void* w, float* y, int32_t row
     float* part = (float*)((char*)workspace + align_up(rp * k_dim * 2 * 2, 256));
     launch_split_act(x, rows, k_dim, a, s);
     GemmPlan plan = gemm_mfma_plan(rows, n, k_dim, 0);
-    launch_gemm_mfma(a, (const bf16*)w, part, n, rp * n, rows, n, k_dim, plan, s);
+    launch_gemm_mfma(a, wseg1(w, n), part, n, rp * n, rows, n, k_dim, plan, s);
     launch_reduce_partials(Partial{part, plan.S, rp * (size_t)n, n}, y, rows, s);
   } else {
     return FIRP_EINVAL;

@@ -99,12 +99,22 @@ struct GemmPlan {
   int S;        // split-K factor
   int k_per;    // K elements per split (multiple of 64)
   int nt;       // 16-row activation tiles
+  int nw;       // waves per workgroup (each owns 32 rows of W): 4, 8 or 16
   int grid;
 };
+#define FIRP_GEMM_NW 4
+GemmPlan gemm_mfma_plan_ex(int rows, int n, int K, int S, int nw);
 bool gemm_mfma_supported(int rows, int n, int K);
 GemmPlan gemm_mfma_plan(int rows, int n, int K, int force_split);  // force_split 0 = choose
+// Weight operand: up to three [n_i][K] matrices stacked along n (rows [0,n0) from w0, the next
+// n1 from w1, the rest from w2).  A single matrix has n0 >= n.
+struct WSeg {
+  const bf16 *w0, *w1, *w2;
+  int n0, n1;
+};
+inline WSeg wseg1(const void* w, int n) { return WSeg{(const bf16*)w, nullptr, nullptr, n, 0}; }
 // partials[s][r][c] at out + s*part_stride + r*ld + c for c < n
-void launch_gemm_mfma(const Act& x, const bf16* w, float* out, int ld, size_t part_stride, int rows,
+void launch_gemm_mfma(const Act& x, const WSeg& w, float* out, int ld, size_t part_stride, int rows,
                       int n, int K, const GemmPlan& plan, hipStream_t s);
 void launch_split_act(const float* x, int rows, int ld, const Act& out, hipStream_t s);
 void launch_reduce_partials(const Partial& p, float* y, int rows, hipStream_t s);
