@@ -77,6 +77,9 @@ def main() -> int:
     ap.add_argument("--prompt", type=int, default=0, help="prompt length (default: the configuration's)")
     ap.add_argument("--anchors", default="root", choices=["root", "all"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="only run a plain 1 GiB device copy three times (reference for scaling the "
+                         "FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run) and exit")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (the step is a single-GPU kernel path); "
@@ -91,6 +94,14 @@ def main() -> int:
         print("bench.py: no GPU visible", file=sys.stderr)
         return 2
     dev = torch.device("cuda:0")
+    if args.copy_calibration:
+        src = torch.ones(1 << 30, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_bytes": 1 << 30, "copies": 3}))
+        return 0
     cfg = synth.CONFIGS[args.config]
     tree = synth.workload_tree(args.config, args.anchors)
     prompt_len = args.prompt or {"13b": 1024, "7b": 512, "tiny_bf16": 64}[args.config]

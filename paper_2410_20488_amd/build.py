@@ -11,7 +11,7 @@ CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libfirp.so")
 SOURCES = ["engine.hip", "kernels_misc.hip", "gemm_simple.hip", "gemm_mfma.hip", *[f"gemm_mfma_nw{i}.hip" for i in range(2, 9)], "attention_simple.hip", "attention_mfma.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Xclang", "-target-feature", "-Xclang",
-         "-packed-fp32-ops", "-Wno-unused-command-line-argument"]
+         "-packed-fp32-ops", "-Wno-unused-command-line-argument", "-Wno-pass-failed"]
 
 
 def _compile(src: str) -> str:
@@ -34,8 +34,15 @@ def build(verbose: bool = True) -> str:
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError(f"link failed:\n{r.stderr}")
+    # standalone per-kernel benchmark (links the library; used for rocprofv3 counter runs)
+    tool = os.path.join(HERE, "bench_projection")
+    cmd = ["hipcc", *FLAGS, os.path.join(CSRC, "bench_projection.hip"), "-o", tool, f"-L{HERE}", "-lfirp",
+           "-Wl,-rpath,$ORIGIN"]
+    r = subprocess.run(cmd, capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError(f"building bench_projection failed:\n{r.stderr}")
     if verbose:
-        print(f"built {LIB}")
+        print(f"built {LIB} and {tool}")
     return LIB
 
 
