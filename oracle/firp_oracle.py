@@ -59,10 +59,13 @@ def rope_rotate(x: torch.Tensor, pos: torch.Tensor, base: float) -> torch.Tensor
     tree attention preserves)."""
     dh = x.shape[-1]
     half = dh // 2
-    j = torch.arange(half, dtype=x.dtype)
-    inv_freq = base ** (-2.0 * j / dh)
-    ang = pos.to(x.dtype)[:, None] * inv_freq[None, :]          # [T, half]
-    c, s = torch.cos(ang)[:, None, :], torch.sin(ang)[:, None, :]
+    # The angle is a function of the integer position alone; it is evaluated in fp64 and only
+    # cos/sin are rounded to the working dtype (an fp32 product pos * freq at positions in the
+    # thousands would already be off by 1e-4 rad).
+    j = torch.arange(half, dtype=torch.float64)
+    inv_freq = float(base) ** (-2.0 * j / dh)
+    ang = pos.to(torch.float64)[:, None] * inv_freq[None, :]    # [T, half]
+    c, s = torch.cos(ang)[:, None, :].to(x.dtype), torch.sin(ang)[:, None, :].to(x.dtype)
     x1, x2 = x[..., :half], x[..., half:]
     return torch.cat([x1 * c - x2 * s, x2 * c + x1 * s], dim=-1)
 

@@ -46,7 +46,7 @@ __device__ __forceinline__ int global_row(const SeqRows& sr, int b, int local) {
 }
 
 template <int DH>
-__global__ __launch_bounds__(512, 1) void k_attention_mfma(const bf16* __restrict__ qhi, const bf16* __restrict__ qlo,
+__global__ __launch_bounds__(256, 1) void k_attention_mfma(const bf16* __restrict__ qhi, const bf16* __restrict__ qlo,
                                                           int ldq, int n_q_heads, SeqRows sr, int n_local,
                                                           const unsigned long long* __restrict__ row_mask,
                                                           const int* __restrict__ p0v, KvView kv, int chunk,
@@ -104,10 +104,9 @@ __global__ __launch_bounds__(512, 1) void k_attention_mfma(const bf16* __restric
     }
 
     // ---- sweep the chunk, 32 keys per block
-    for (int k0 = key_begin; k0 < key_end; k0 += 32) {
+    auto load_kv = [&](u32x4_t (&kf)[2][DS], u32x4_t (&vf)[DT], int k0) {
       // K rows of the two 16-key tiles: MFMA row m <-> key 8*(m/4) + (m%4) (+4 for the second)
       const int key_a = k0 + 8 * (r16 >> 2) + (r16 & 3);
-      u32x4_t kf[2][DS], vf[DT];
 #pragma unroll
       for (int t2 = 0; t2 < 2; ++t2) {
         const bf16* kr = Kb + (size_t)min(key_a + 4 * t2, kv.slots - 1) * DH + kb * 8;
@@ -116,6 +115,8 @@ __global__ __launch_bounds__(512, 1) void k_attention_mfma(const bf16* __restric
       }
 #pragma unroll
       for (int dt = 0; dt < DT; ++dt) vf[dt] = *(const u32x4_t*)(Vt + (size_t)(dt * 16 + r16) * kv.slots + k0 + 8 * kb);
+    };
+    auto block = [&](u32x4_t (&kf)[2][DS], u32x4_t (&vf)[DT], int k0) {
       const bool need_mask = k0 + 32 > p0;
 #pragma unroll
       for (int p = 0; p < PAIRS; ++p) {
@@ -183,7 +184,25 @@ __global__ __launch_bounds__(512, 1) void k_attention_mfma(const bf16* __restric
           o[p][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(vf[dt]), as_bf16x8(pl), o[p][dt], 0, 0, 0);
         }
       }
+    };
+    // three register sets: the loads of blocks i+1 and i+2 are in flight while block i is multiplied
+    u32x4_t kfa[2][DS], vfa[DT], kfb[2][DS], vfb[DT], kfc[2][DS], vfc[DT];
+    const int k_last = max(key_begin, ((key_end - 1) >> 5) << 5);   // start of the last block
+    if (key_begin < key_end) {
+      load_kv(kfa, vfa, key_begin);
+      load_kv(kfb, vfb, min(key_begin + 32, k_last));
     }
+    int k0 = key_begin;
+    for (; k0 + 64 < key_end; k0 += 96) {
+      load_kv(kfc, vfc, k0 + 64);
+      block(kfa, vfa, k0);
+      load_kv(kfa, vfa, min(k0 + 96, k_last));
+      block(kfb, vfb, k0 + 32);
+      load_kv(kfb, vfb, min(k0 + 128, k_last));
+      block(kfc, vfc, k0 + 64);
+    }
+    if (k0 < key_end) block(kfa, vfa, k0);
+    if (k0 + 32 < key_end) block(kfb, vfb, k0 + 32);
 
     // ---- leave this split's partial result: lane holds O[row r16][dim dt*16 + 4*kb + i]
 #pragma unroll
@@ -204,10 +223,12 @@ __global__ __launch_bounds__(512, 1) void k_attention_mfma(const bf16* __restric
 }
 
 // Merge the splits of one (row, q head): O = sum_s 2^(m_s - M) o_s / sum_s 2^(m_s - M) l_s.
+// blockDim = (dh/4, heads per block); blockIdx = (row, head group).
 template <bool SPLIT>
 __global__ void k_attn_combine(const float* __restrict__ part_o, const float* __restrict__ part_ml, int splits,
                                int n_q_heads, int dh, Act out) {
-  int r = blockIdx.x, h = blockIdx.y;
+  int r = blockIdx.x, h = blockIdx.y * blockDim.y + threadIdx.y;
+  if (h >= n_q_heads) return;
   size_t base = ((size_t)r * n_q_heads + h) * splits;
   float M = -__builtin_inff();
   for (int s = 0; s < splits; ++s) M = fmaxf(M, part_ml[(base + s) * 2]);
@@ -215,7 +236,6 @@ __global__ void k_attn_combine(const float* __restrict__ part_o, const float* __
   for (int s = 0; s < splits; ++s) L += exp2f(part_ml[(base + s) * 2] - M) * part_ml[(base + s) * 2 + 1];
   float inv = 1.0f / L;
   int d = threadIdx.x * 4;
-  if (d >= dh) return;
   float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
   for (int s = 0; s < splits; ++s) {
     float w = exp2f(part_ml[(base + s) * 2] - M);
@@ -243,16 +263,16 @@ void launch_attention_mfma(const Act& q, int rows, int n_q_heads, int B, int n_r
   const int n_local = n_real_per_seq + n_pseudo_per_seq;
   const int dh = kv.head_dim;
   SeqRows sr{n_real_per_seq, n_pseudo_per_seq, B * n_real_per_seq};
-  // chunks of whole 32-key blocks; enough workgroups to cover the CUs about twice
+  // chunks of whole 32-key blocks; about one workgroup per CU
   int n_keys = max_ctx_now + n_local;
   int blocks = (n_keys + 31) / 32;
-  int want = std::max(1, 512 / std::max(1, kv.n_kv_heads * B));
+  int want = std::max(1, 256 / std::max(1, kv.n_kv_heads * B));
   int splits = std::max(1, std::min({want, blocks, FIRP_ATTN_MAX_SPLITS}));
   int chunk = ((blocks + splits - 1) / splits) * 32;
   splits = (n_keys + chunk - 1) / chunk;
   const int G = n_q_heads / kv.n_kv_heads;
   int n_pairs = ((n_local + 15) / 16) * G;
-  int n_waves = std::max(1, std::min(8, (n_pairs + PAIRS - 1) / PAIRS));
+  int n_waves = std::max(1, std::min(4, (n_pairs + PAIRS - 1) / PAIRS));
   float* part_o = scratch;
   float* part_ml = scratch + (size_t)rows * n_q_heads * FIRP_ATTN_MAX_SPLITS * dh;
   dim3 g(splits, kv.n_kv_heads, B), blk(64 * n_waves);
@@ -262,7 +282,8 @@ void launch_attention_mfma(const Act& q, int rows, int n_q_heads, int B, int n_r
     hipLaunchKernelGGL(k_attention_mfma<64>, g, blk, 0, s, q.hi, q.lo, q.ld, n_q_heads, sr, n_local, rt.mask, p0, kv, chunk, part_o, part_ml, splits);
   else
     hipLaunchKernelGGL(k_attention_mfma<32>, g, blk, 0, s, q.hi, q.lo, q.ld, n_q_heads, sr, n_local, rt.mask, p0, kv, chunk, part_o, part_ml, splits);
-  dim3 gc(rows, n_q_heads), bc(std::max(dh / 4, 1));
+  int hpb = std::max(1, 256 / (dh / 4));
+  dim3 gc(rows, (n_q_heads + hpb - 1) / hpb), bc(dh / 4, hpb);
   hipLaunchKernelGGL(k_attn_combine<true>, gc, bc, 0, s, part_o, part_ml, splits, n_q_heads, dh, out);
 }
 

@@ -122,4 +122,16 @@ __device__ __forceinline__ float block_sum_256(float v, float* smem4) {
   return smem4[0] + smem4[1] + smem4[2] + smem4[3];
 }
 
+// block-wide sum for any blockDim.x that is a multiple of 64 (up to 16 waves)
+__device__ __forceinline__ float block_sum(float v, float* smem16) {
+  v = wave_sum(v);
+  int w = threadIdx.x >> 6, nw = blockDim.x >> 6;
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) smem16[w] = v;
+  __syncthreads();
+  float t = 0.f;
+  for (int i = 0; i < nw; ++i) t += smem16[i];
+  return t;
+}
+
 }  // namespace firp

@@ -51,6 +51,7 @@ struct firp_ctx {
   int attn_kind = 0;    // 0 plain, 1 MFMA flash-decode (needs the bf16 planes of q)
   bool cache_clean = false;  // the KV cache holds only finite values (zero-filled once)
   float* attn_scratch = nullptr;
+  float2* rope_tab = nullptr;  // [rows][dh/2] (cos, sin) of the running step
   hipStream_t stream = nullptr;
   // weights
   const void* embed = nullptr;
@@ -135,6 +136,7 @@ size_t carve(firp_ctx* c, char* base) {
   c->part = cv.take<float>(c->part_elems);
   c->logits = cv.take<float>((size_t)Rp * d.vocab);
   c->attn_scratch = cv.take<float>(attention_mfma_scratch_floats(Rp, d.n_q_heads, d.head_dim));
+  c->rope_tab = cv.take<float2>((size_t)Rp * d.head_dim / 2);
   auto act = [&](Act& a, int ld) {
     a.ld = ld;
     a.f32 = cv.take<float>((size_t)Rp * ld);
@@ -284,6 +286,7 @@ firp_status forward(firp_ctx* c, int B, int rows_lo, int rows_hi, int n_anchor_r
   const bool sp = c->split;
   const int qd = d.n_q_heads * d.head_dim, kvd = d.n_kv_heads * d.head_dim;
   launch_embed(c->embed, c->dtype, c->st.tok, rows_lo, d.d_model, c->x, s);
+  launch_rope_table(rt, c->st.p0, rows_hi, d.head_dim, d.rope_base, c->rope_tab, s);
   Partial pending{};  // projection output not yet added to the residual stream
   int pending_rows = 0;
   for (int layer = 0; layer <= d.n_layers; ++layer) {
@@ -318,7 +321,7 @@ firp_status forward(firp_ctx* c, int B, int rows_lo, int rows_hi, int n_anchor_r
     launch_add_rmsnorm(c->x, pending, rows, d.d_model, c->n1[layer], c->dtype, d.rms_eps, c->act_d, sp, s);
     Partial q = project_stacked(c, c->act_d, c->wq[layer], qd, c->wk[layer], kvd, c->wv[layer], kvd, rows, d.d_model);
     KvView kv = kv_view(c, layer);
-    launch_rope_kv(q, rows, d.n_q_heads, rt, c->st.p0, d.rope_base, c->act_q, sp, kv, c->dtype, s);
+    launch_rope_kv(q, rows, d.n_q_heads, rt, c->st.p0, c->rope_tab, c->act_q, sp, kv, c->dtype, s);
     if (c->attn_kind == 1 && sp)
       launch_attention_mfma(c->act_q, rows, d.n_q_heads, B, n_local_lo, n_local - n_local_lo, rt, c->st.p0,
                             max_ctx_now, kv, c->attn_scratch, c->act_o, s);

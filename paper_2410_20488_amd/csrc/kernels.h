@@ -54,8 +54,10 @@ void launch_add_rmsnorm(float* x, const Partial& part, int rows, int d, const vo
 // Only the residual update, no norm output (used before the projection at the FIRP layer).
 void launch_add_partial(float* x, const Partial& part, int rows, int d, hipStream_t s);
 // qkv partials -> rotary q (activation planes, [rows][Hq*dh]) and K / V^T into the cache.
+void launch_rope_table(const RowTab& rt, const int* p0, int rows, int head_dim, float rope_base,
+                       float2* tab, hipStream_t s);   // cos/sin of every row's position, once per step
 void launch_rope_kv(const Partial& qkv, int rows, int n_q_heads, const RowTab& rt, const int* p0,
-                    float rope_base, const Act& q_out, bool split, const KvView& kv, int dtype,
+                    const float2* tab, const Act& q_out, bool split, const KvView& kv, int dtype,
                     hipStream_t s);
 void launch_swiglu(const Partial& gate_up, int rows, int d_ffn, const Act& out, bool split,
                    hipStream_t s);

@@ -1,6 +1,8 @@
 // Everything of the step that is not a projection or attention: candidate fill, embedding
 // gather, fused residual-add + RMSNorm, rotary + KV append, SwiGLU, the FIRP map's gather /
 // scatter, argmax / top-b over the logits, greedy verification, KV compaction.
+#include <algorithm>
+
 #include "kernels.h"
 
 namespace firp {
@@ -50,13 +52,14 @@ void launch_embed(const void* embed, int dtype, const int* tok, int rows, int d,
 
 // ------------------------------------------------------------------------------------------
 // Residual update + RMSNorm: x[r] += sum_s part[s][r]; act[r] = x[r] / sqrt(mean(x^2)+eps) * g.
-// One workgroup per row; the row stays in registers between the two passes (d <= 8192),
+// One workgroup (up to 1024 threads) per row; the row stays in registers between the two passes,
 // all loads of a thread are independent 128-bit loads.
 template <typename GT, bool SPLIT, bool NORM>
-__global__ __launch_bounds__(256) void k_add_rmsnorm(float* x, Partial part, int d,
-                                                     const GT* __restrict__ gain, float eps, Act out) {
-  __shared__ float red[4];
-  constexpr int MAXV = 8;  // float4 per thread
+__global__ __launch_bounds__(1024) void k_add_rmsnorm(float* x, Partial part, int d,
+                                                      const GT* __restrict__ gain, float eps, Act out) {
+  __shared__ float red[16];
+  constexpr int MAXV = 2;  // float4 per thread: d <= 8192 with 1024 threads
+  const int T = blockDim.x;
   int r = blockIdx.x;
   float4* xr = (float4*)(x + (size_t)r * d);
   const int nv = d >> 2;
@@ -64,17 +67,17 @@ __global__ __launch_bounds__(256) void k_add_rmsnorm(float* x, Partial part, int
   float ss = 0.f;
 #pragma unroll
   for (int e = 0; e < MAXV; ++e) {
-    int i = threadIdx.x + e * 256;
+    int i = threadIdx.x + e * T;
     if (i < nv) {
       float4 a = xr[i];
       if (part.p) {
-        const float4* pp = (const float4*)(part.p + (size_t)r * part.ld) + i;
-        float4 q[8];
+        const float* pp = part.p + (size_t)r * part.ld + (size_t)i * 4;
+        float4 q[16];
 #pragma unroll
-        for (int sp = 0; sp < 8; ++sp)
-          if (sp < part.S) q[sp] = *(const float4*)((const float*)pp + (size_t)sp * part.stride);
+        for (int sp = 0; sp < 16; ++sp)
+          if (sp < part.S) q[sp] = *(const float4*)(pp + (size_t)sp * part.stride);
 #pragma unroll
-        for (int sp = 0; sp < 8; ++sp)
+        for (int sp = 0; sp < 16; ++sp)
           if (sp < part.S) {
             a.x += q[sp].x;
             a.y += q[sp].y;
@@ -88,11 +91,11 @@ __global__ __launch_bounds__(256) void k_add_rmsnorm(float* x, Partial part, int
     }
   }
   if constexpr (NORM) {
-    ss = block_sum_256(ss, red);
+    ss = block_sum(ss, red);
     float inv = 1.0f / sqrtf(ss / (float)d + eps);
 #pragma unroll
     for (int e = 0; e < MAXV; ++e) {
-      int i = threadIdx.x + e * 256;
+      int i = threadIdx.x + e * T;
       if (i < nv) {
         size_t o = (size_t)r * out.ld + (size_t)i * 4;
         act_store4<SPLIT>(out, o, v[e].x * inv * to_f32(gain[i * 4 + 0]), v[e].y * inv * to_f32(gain[i * 4 + 1]),
@@ -102,9 +105,14 @@ __global__ __launch_bounds__(256) void k_add_rmsnorm(float* x, Partial part, int
   }
 }
 
+static int norm_threads(int d) {
+  int t = ((d / 4 + 1) / 2 + 63) / 64 * 64;   // two float4 per thread
+  return std::max(64, std::min(1024, t));
+}
+
 void launch_add_rmsnorm(float* x, const Partial& part, int rows, int d, const void* gain,
                         int dtype, float eps, const Act& out, bool split, hipStream_t s) {
-  dim3 g(rows), b(256);
+  dim3 g(rows), b(norm_threads(d));
   if (dtype == DT_BF16) {
     if (split)
       hipLaunchKernelGGL((k_add_rmsnorm<bf16, true, true>), g, b, 0, s, x, part, d, (const bf16*)gain, eps, out);
@@ -117,64 +125,78 @@ void launch_add_rmsnorm(float* x, const Partial& part, int rows, int d, const vo
 
 void launch_add_partial(float* x, const Partial& part, int rows, int d, hipStream_t s) {
   Act none{};
-  hipLaunchKernelGGL((k_add_rmsnorm<float, false, false>), dim3(rows), dim3(256), 0, s, x, part, d,
+  hipLaunchKernelGGL((k_add_rmsnorm<float, false, false>), dim3(rows), dim3(norm_threads(d)), 0, s, x, part, d,
                      (const float*)nullptr, 0.f, none);
 }
 
 // ------------------------------------------------------------------------------------------
 // Rotary embedding (half-split pairs (j, j+dh/2), angle pos * base^(-2j/dh)) on q and k at the
 // row's position id p0 + pos_off (tree nodes keep their original positions; siblings share
-// one), then K and V^T go to cache slot p0 + local.  The angle is formed in fp64: at positions
-// in the thousands an fp32 product would already be off by 1e-4 rad.
+// one), then K and V^T go to cache slot p0 + local.  cos/sin come from a per-step table whose
+// angles are formed in fp64: at positions in the thousands an fp32 product would already be
+// off by 1e-4 rad.
+__global__ void k_rope_table(RowTab rt, const int* __restrict__ p0, int half, float rope_base, float2* tab) {
+  int r = blockIdx.x, j = threadIdx.x;
+  if (j >= half) return;
+  double inv_freq = exp2(-(double)j / (double)half * log2((double)rope_base));
+  double ang = (double)(p0[rt.seq[r]] + rt.pos_off[r]) * inv_freq;
+  double sd, cd;
+  sincos(ang, &sd, &cd);
+  tab[(size_t)r * half + j] = make_float2((float)cd, (float)sd);
+}
+
+void launch_rope_table(const RowTab& rt, const int* p0, int rows, int head_dim, float rope_base, float2* tab,
+                       hipStream_t s) {
+  hipLaunchKernelGGL(k_rope_table, dim3(rows), dim3(head_dim / 2), 0, s, rt, p0, head_dim / 2, rope_base, tab);
+}
+
+// blockDim = (dh/2, heads per block); blockIdx = (row, head group)
 template <typename KT, bool SPLIT>
 __global__ void k_rope_kv(Partial qkv, int n_q_heads, RowTab rt, const int* __restrict__ p0,
-                          float rope_base, Act q_out, KvView kv) {
-  int r = blockIdx.x, h = blockIdx.y, j = threadIdx.x;
+                          const float2* __restrict__ tab, Act q_out, KvView kv) {
+  int r = blockIdx.x, h = blockIdx.y * blockDim.y + threadIdx.y, j = threadIdx.x;
   int dh = kv.head_dim, half = dh >> 1, Hkv = kv.n_kv_heads;
+  if (h >= n_q_heads + 2 * Hkv) return;
   int b = rt.seq[r];
-  int base_pos = p0[b];
   size_t row_off = (size_t)r * qkv.ld;
+  float x1 = partial_sum(qkv, row_off + (size_t)h * dh + j);
+  float x2 = partial_sum(qkv, row_off + (size_t)h * dh + j + half);
   if (h < n_q_heads + Hkv) {
-    double inv_freq = exp2(-2.0 * (double)j / (double)dh * log2((double)rope_base));
-    double ang = (double)(base_pos + rt.pos_off[r]) * inv_freq;
-    double sd, cd;
-    sincos(ang, &sd, &cd);
-    float c = (float)cd, sn = (float)sd;
-    float x1 = partial_sum(qkv, row_off + (size_t)h * dh + j);
-    float x2 = partial_sum(qkv, row_off + (size_t)h * dh + j + half);
-    float y1 = x1 * c - x2 * sn, y2 = x2 * c + x1 * sn;
+    float2 cs = tab[(size_t)r * half + j];
+    float y1 = x1 * cs.x - x2 * cs.y, y2 = x2 * cs.x + x1 * cs.y;
     if (h < n_q_heads) {
       act_store<SPLIT>(q_out, (size_t)r * q_out.ld + (size_t)h * dh + j, y1);
       act_store<SPLIT>(q_out, (size_t)r * q_out.ld + (size_t)h * dh + j + half, y2);
     } else {
       int hk = h - n_q_heads;
-      size_t slot = (size_t)(base_pos + rt.local[r]);
+      size_t slot = (size_t)(p0[b] + rt.local[r]);
       KT* krow = (KT*)kv.k + (size_t)b * kv.seq_stride + ((size_t)hk * kv.slots + slot) * dh;
       store_elt<KT>(krow + j, y1);
       store_elt<KT>(krow + j + half, y2);
     }
   } else {
     int hv = h - n_q_heads - Hkv;
-    size_t slot = (size_t)(base_pos + rt.local[r]);
+    size_t slot = (size_t)(p0[b] + rt.local[r]);
     KT* vt = (KT*)kv.v + (size_t)b * kv.seq_stride + (size_t)hv * dh * kv.slots + slot;
-    float v1 = partial_sum(qkv, row_off + (size_t)(n_q_heads + Hkv + hv) * dh + j);
-    float v2 = partial_sum(qkv, row_off + (size_t)(n_q_heads + Hkv + hv) * dh + j + half);
-    store_elt<KT>(vt + (size_t)j * kv.slots, v1);
-    store_elt<KT>(vt + (size_t)(j + half) * kv.slots, v2);
+    store_elt<KT>(vt + (size_t)j * kv.slots, x1);
+    store_elt<KT>(vt + (size_t)(j + half) * kv.slots, x2);
   }
 }
 
 void launch_rope_kv(const Partial& qkv, int rows, int n_q_heads, const RowTab& rt, const int* p0,
-                    float rope_base, const Act& q_out, bool split, const KvView& kv, int dtype,
+                    const float2* tab, const Act& q_out, bool split, const KvView& kv, int dtype,
                     hipStream_t s) {
-  dim3 g(rows, n_q_heads + 2 * kv.n_kv_heads), b(kv.head_dim / 2);
+  int half = kv.head_dim / 2;
+  int hpb = std::max(1, 256 / half);
+  int heads = n_q_heads + 2 * kv.n_kv_heads;
+  dim3 g(rows, (heads + hpb - 1) / hpb), b(half, hpb);
   if (dtype == DT_BF16) {
     if (split)
-      hipLaunchKernelGGL((k_rope_kv<bf16, true>), g, b, 0, s, qkv, n_q_heads, rt, p0, rope_base, q_out, kv);
+      hipLaunchKernelGGL((k_rope_kv<bf16, true>), g, b, 0, s, qkv, n_q_heads, rt, p0, tab, q_out, kv);
     else
-      hipLaunchKernelGGL((k_rope_kv<bf16, false>), g, b, 0, s, qkv, n_q_heads, rt, p0, rope_base, q_out, kv);
+      hipLaunchKernelGGL((k_rope_kv<bf16, false>), g, b, 0, s, qkv, n_q_heads, rt, p0, tab, q_out, kv);
   } else {
-    hipLaunchKernelGGL((k_rope_kv<float, false>), g, b, 0, s, qkv, n_q_heads, rt, p0, rope_base, q_out, kv);
+    hipLaunchKernelGGL((k_rope_kv<float, false>), g, b, 0, s, qkv, n_q_heads, rt, p0, tab, q_out, kv);
   }
 }
 
@@ -249,8 +271,7 @@ void launch_scatter_pseudo(const Partial& y, int n_anchor_rows, int d, int k, in
 
 // ------------------------------------------------------------------------------------------
 // Greedy token of real rows, top-b of pseudo rows.  Order: larger logit first, ties to the
-// lower token id.  One block per row; pass p finds the best entry that comes strictly after
-// the winner of pass p-1 in that order.
+// lower token id.  One block per row.
 struct Best {
   float v;
   int id;
@@ -259,55 +280,72 @@ __device__ __forceinline__ bool better(float v, int id, const Best& o) {
   return v > o.v || (v == o.v && id < o.id);
 }
 
+// One pass over the row: every thread keeps the best BM entries of its strided share in
+// registers (sorted insertion), then BM rounds of a block-wide arg-best over the threads'
+// current heads pick the row's top entries in order.
+template <int BM>
 __global__ __launch_bounds__(256) void k_argmax_topb(Partial lg, float* logits_out, int real_rows,
                                                      int vocab, int b_max, int* amax, int* top) {
   __shared__ float sv[256];
   __shared__ int si[256];
-  int r = blockIdx.x;
-  size_t off = (size_t)r * lg.ld;
-  if (logits_out && (lg.S > 1 || logits_out != lg.p)) {
-    for (int t = threadIdx.x; t < vocab; t += 256) logits_out[(size_t)r * vocab + t] = partial_sum(lg, off + t);
-    __syncthreads();
-  }
-  const float* row = logits_out ? logits_out + (size_t)r * vocab : nullptr;
-  int passes = (r < real_rows) ? 1 : b_max;
-  Best prev{__builtin_inff(), -1};
-  for (int p = 0; p < passes; ++p) {
-    Best best{-__builtin_inff(), 0x7fffffff};
-    for (int t = threadIdx.x; t < vocab; t += 256) {
-      float v = row ? row[t] : partial_sum(lg, off + t);
-      bool after_prev = (p == 0) || v < prev.v || (v == prev.v && t > prev.id);
-      if (after_prev && better(v, t, best)) best = Best{v, t};
+  const int r = blockIdx.x, tid = threadIdx.x;
+  const size_t off = (size_t)r * lg.ld;
+  const bool copy = logits_out && (lg.S > 1 || logits_out != lg.p);
+  const int want = (r < real_rows) ? 1 : b_max;
+  Best mine[BM];
+#pragma unroll
+  for (int e = 0; e < BM; ++e) mine[e] = Best{-__builtin_inff(), 0x7fffffff};
+  for (int t = tid; t < vocab; t += 256) {
+    float v = partial_sum(lg, off + t);
+    if (copy) logits_out[(size_t)r * vocab + t] = v;
+    if (better(v, t, mine[BM - 1])) {
+      mine[BM - 1] = Best{v, t};
+#pragma unroll
+      for (int e = BM - 1; e > 0; --e)
+        if (better(mine[e].v, mine[e].id, mine[e - 1])) {
+          Best tmp = mine[e - 1];
+          mine[e - 1] = mine[e];
+          mine[e] = tmp;
+        }
     }
-    sv[threadIdx.x] = best.v;
-    si[threadIdx.x] = best.id;
+  }
+  for (int p = 0; p < want; ++p) {
+    sv[tid] = mine[0].v;
+    si[tid] = mine[0].id;
     __syncthreads();
     for (int w = 128; w > 0; w >>= 1) {
-      if (threadIdx.x < w) {
-        Best o{sv[threadIdx.x + w], si[threadIdx.x + w]};
-        Best m{sv[threadIdx.x], si[threadIdx.x]};
+      if (tid < w) {
+        Best o{sv[tid + w], si[tid + w]};
+        Best m{sv[tid], si[tid]};
         if (better(o.v, o.id, m)) {
-          sv[threadIdx.x] = o.v;
-          si[threadIdx.x] = o.id;
+          sv[tid] = o.v;
+          si[tid] = o.id;
         }
       }
       __syncthreads();
     }
-    prev = Best{sv[0], si[0]};
+    int win = si[0];
     __syncthreads();
-    if (threadIdx.x == 0) {
+    if (mine[0].id == win) {  // the owner pops its head
+#pragma unroll
+      for (int e = 0; e + 1 < BM; ++e) mine[e] = mine[e + 1];
+      mine[BM - 1] = Best{-__builtin_inff(), 0x7fffffff};
+    }
+    if (tid == 0) {
       if (r < real_rows)
-        amax[r] = prev.id;
+        amax[r] = win;
       else
-        top[(size_t)(r - real_rows) * b_max + p] = prev.id;
+        top[(size_t)(r - real_rows) * b_max + p] = win;
     }
   }
 }
 
 void launch_argmax_topb(const Partial& logits, float* logits_out, int real_rows, int rows,
                         int vocab, int b_max, int* amax, int* top, hipStream_t s) {
-  hipLaunchKernelGGL(k_argmax_topb, dim3(rows), dim3(256), 0, s, logits, logits_out, real_rows, vocab,
-                     b_max, amax, top);
+  if (b_max <= 8)
+    hipLaunchKernelGGL(k_argmax_topb<8>, dim3(rows), dim3(256), 0, s, logits, logits_out, real_rows, vocab, b_max, amax, top);
+  else
+    hipLaunchKernelGGL(k_argmax_topb<16>, dim3(rows), dim3(256), 0, s, logits, logits_out, real_rows, vocab, b_max, amax, top);
 }
 
 // ------------------------------------------------------------------------------------------

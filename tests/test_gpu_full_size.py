@@ -1,0 +1,26 @@
+"""Parity at the benchmark's full sizes: the LLaMA-2-7B- and 13B-shaped models at full depth,
+their prompts and draft trees, in the launch configuration bench.py times, against the CPU
+oracle run on the same weights (all logits of every step, tokens, path, drafts)."""
+import pytest
+import torch
+
+from paper_2410_20488_amd import synth
+from tests.gpu_common import run_lockstep
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.mark.parametrize("name,prompt_len,n_steps", [("7b", 512, 4), ("13b", 1024, 3)])
+def test_full_depth_model_matches_oracle(name, prompt_len, n_steps, progress):
+    assert torch.cuda.is_available()
+    dev = torch.device("cuda:0")
+    cfg = synth.CONFIGS[name]
+    progress(f"{name}: generating weights")
+    w = synth.make_weights(cfg, dev)
+    tree = synth.workload_tree(name)
+    rep, eng, orc = run_lockstep(cfg, w, tree, prompt_len=prompt_len, n_steps=n_steps, tol=2e-2,
+                                 progress=progress, max_rows=128)
+    progress(f"{name}: max logit err {rep.max_logit_err:.3e}, ties {rep.tie_ambiguous}, "
+             f"accepted histogram {rep.accepted_hist}")
+    assert rep.steps == n_steps
+    assert rep.tie_ambiguous <= n_steps        # near-ties are rare, not the rule
