@@ -185,24 +185,18 @@ __global__ __launch_bounds__(256, 1) void k_attention_mfma(const bf16* __restric
         }
       }
     };
-    // three register sets: the loads of blocks i+1 and i+2 are in flight while block i is multiplied
-    u32x4_t kfa[2][DS], vfa[DT], kfb[2][DS], vfb[DT], kfc[2][DS], vfc[DT];
+    // two register sets: the loads of block i+1 are in flight while block i is multiplied
+    u32x4_t kfa[2][DS], vfa[DT], kfb[2][DS], vfb[DT];
     const int k_last = max(key_begin, ((key_end - 1) >> 5) << 5);   // start of the last block
-    if (key_begin < key_end) {
-      load_kv(kfa, vfa, key_begin);
-      load_kv(kfb, vfb, min(key_begin + 32, k_last));
-    }
+    if (key_begin < key_end) load_kv(kfa, vfa, key_begin);
     int k0 = key_begin;
-    for (; k0 + 64 < key_end; k0 += 96) {
-      load_kv(kfc, vfc, k0 + 64);
+    for (; k0 + 32 < key_end; k0 += 64) {
+      load_kv(kfb, vfb, k0 + 32);
       block(kfa, vfa, k0);
-      load_kv(kfa, vfa, min(k0 + 96, k_last));
+      load_kv(kfa, vfa, min(k0 + 64, k_last));
       block(kfb, vfb, k0 + 32);
-      load_kv(kfb, vfb, min(k0 + 128, k_last));
-      block(kfc, vfc, k0 + 64);
     }
     if (k0 < key_end) block(kfa, vfa, k0);
-    if (k0 + 32 < key_end) block(kfb, vfb, k0 + 32);
 
     // ---- leave this split's partial result: lane holds O[row r16][dim dt*16 + 4*kb + i]
 #pragma unroll

@@ -86,7 +86,7 @@ def run_lockstep(cfg, weights_gpu, tree: synth.Tree, *, prompt_len: int, n_steps
             for _ in range(min(cfg.k, max(depth))):
                 truth += look.step(parent=[-1], rank=[0], anchor=[0]).tokens
             inject = synth.prompt_tokens(step, tree.n_nodes, cfg.vocab, stream=5).tolist()
-            want_len = 1 + (step // 3) % (len(truth) + 1)
+            want_len = 1 + (1 + step // 3) % (len(truth) + 1)
             for v in range(1, tree.n_nodes):
                 if inject[v] in truth:
                     inject[v] = (inject[v] + 1) % cfg.vocab
