@@ -19,6 +19,10 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E bandwidth
+# HBM bytes moved per algorithmic weight byte by the projection kernel at the 13B shapes,
+# weighted by each shape's share of a step: (FETCH_SIZE + WRITE_SIZE) / weights from the
+# rocprofv3 --pmc runs summarised in profiles/k_gemm_mfma_13b_shapes_hbm_traffic.md
+GEMM_TRAFFIC_RATIO_13B = 1.116
 
 
 def algorithmic_bytes(cfg, n_nodes: int, t_hi: int, ctx: int) -> float:
@@ -36,6 +40,7 @@ def cpu_baseline(cfg, weights_gpu, tree, prompt, budget_note: str):
     """Time the CPU oracle, as it stands, on a bounded sample of the same workload: the same
     widths, prompt and tree with only the first 2 and the first 4 of the layers; the per-layer
     cost from the difference is extrapolated to the full depth."""
+    # (about 20 s of CPU work including the two prefills)
     import torch
     from paper_2410_20488_amd import synth
     from tests.helpers import make_oracle
@@ -55,16 +60,19 @@ def cpu_baseline(cfg, weights_gpu, tree, prompt, budget_note: str):
         o.prefill(prompt)
         args = dict(parent=list(tree.parent), rank=list(tree.rank), anchor=list(tree.anchor))
         t0 = time.perf_counter()
-        o.step(**args)
-        return time.perf_counter() - t0
+        for _ in range(3):
+            o.step(**args)
+        return (time.perf_counter() - t0) / 3.0
 
-    t2 = sample(2)
-    t4 = sample(4)
-    per_layer = max((t4 - t2) / 2.0, 0.0)
-    full = t2 + per_layer * (cfg.n_layers - 2)
+    la, lb = 4, 8
+    t2 = sample(la)
+    t4 = sample(lb)
+    per_layer = max((t4 - t2) / float(lb - la), 0.0)
+    full = t2 + per_layer * (cfg.n_layers - la)
     return {"value": round(full * 1e3, 1), "unit": "ms/step", "cores": torch.get_num_threads(), "kind": "oracle",
-            "sample": f"fp32 oracle step at the full widths, prompt and tree with 2 and with 4 of the "
-                      f"{cfg.n_layers} layers ({t2:.2f} s, {t4:.2f} s); per-layer cost extrapolated to full depth"
+            "sample": f"fp32 oracle: 3 steps each at the full widths, prompt and tree with {la} and with {lb} of the "
+                      f"{cfg.n_layers} layers ({t2:.2f} s and {t4:.2f} s per step); per-layer cost extrapolated to "
+                      f"full depth"
                       + budget_note}
 
 
@@ -156,7 +164,9 @@ def main() -> int:
         "tokens_per_step": round(tokens / args.steps, 3),
         "setup_s": round(setup_s, 1),
         "roofline": {"bound": "hbm", "kernel": "k_gemm_mfma", "achieved": round(gemm_gbs, 1), "peak": HBM_PEAK_GBS,
-                     "unit": "GB/s", "frac": round(gemm_gbs / HBM_PEAK_GBS, 4), "traffic": None,
+                     "unit": "GB/s", "frac": round(gemm_gbs / HBM_PEAK_GBS, 4),
+                     "traffic": (round(GEMM_TRAFFIC_RATIO_13B * gemm_bytes / max(launches, 1), 0)
+                                 if args.config == "13b" else None),
                      "launches_timed": launches,
                      "avg_launch_us": round(gemm_ms * 1e3 / max(launches, 1), 2),
                      "algorithmic_MB_per_launch": round(gemm_bytes / max(launches, 1) / 1e6, 2),
