@@ -13,6 +13,10 @@
 
 using namespace firp;
 
+// Rows of the partial-sum buffer are padded by one 128-byte line: projection widths are
+// multiples of 1024 floats, and rows a multiple of 4 KB apart would all fall on one memory channel.
+#define FIRP_PART_PAD 32
+
 namespace {
 
 std::string g_init_error;
@@ -192,7 +196,7 @@ void setup_geometry(firp_ctx* c, const firp_model_desc* d, int k) {
   c->kv_seq_stride = (size_t)d->n_layers * c->kv_layer_stride;
   // split-K partial sums: the widest projection output times the largest split factor used
   size_t widest = std::max<size_t>({(size_t)d->vocab, (size_t)2 * d->d_ffn, (size_t)c->qkv_ld, (size_t)d->d_model});
-  c->part_elems = (size_t)c->Rpad * widest * 8;
+  c->part_elems = (size_t)c->Rpad * (widest + FIRP_PART_PAD) * 8;
 }
 
 #define HIPCHK(call)                                                                         \
@@ -222,8 +226,8 @@ TreeTab tree_tab(const firp_ctx* c, int N, int P) {
 Partial project(firp_ctx* c, const Act& in, const void* w, int rows, int n, int K, int ld, int col,
                 const Partial* like) {
   Partial out;
-  out.ld = ld;
-  out.stride = (size_t)c->Rpad * ld;
+  out.ld = ld + FIRP_PART_PAD;
+  out.stride = (size_t)c->Rpad * out.ld;
   out.p = c->part;
   if (c->gemm_kind == 1 && gemm_mfma_supported(rows, n, K)) {
     GemmPlan plan = gemm_mfma_plan(rows, n, K, like ? like->S : 0);
@@ -231,7 +235,7 @@ Partial project(firp_ctx* c, const Act& in, const void* w, int rows, int n, int 
       plan = gemm_mfma_plan(rows, n, K, (int)std::max<size_t>(1, c->part_elems / out.stride));
     bool timed = c->time_gemm && c->ev_used + 2 <= c->ev.size();
     if (timed) (void)hipEventRecord(c->ev[c->ev_used++], c->stream);
-    launch_gemm_mfma(in, wseg1(w, n), c->part + col, ld, out.stride, rows, n, K, plan, c->stream);
+    launch_gemm_mfma(in, wseg1(w, n), c->part + col, out.ld, out.stride, rows, n, K, plan, c->stream);
     if (timed) {
       (void)hipEventRecord(c->ev[c->ev_used++], c->stream);
       c->gemm_bytes += 2.0 * (double)n * (double)K;
@@ -239,7 +243,7 @@ Partial project(firp_ctx* c, const Act& in, const void* w, int rows, int n, int 
     }
     out.S = plan.S;
   } else {
-    launch_gemm_simple(in.f32, in.ld, w, c->dtype, c->part + col, ld, rows, n, K, c->stream);
+    launch_gemm_simple(in.f32, in.ld, w, c->dtype, c->part + col, out.ld, rows, n, K, c->stream);
     out.S = 1;
   }
   return out;
@@ -252,8 +256,8 @@ Partial project_stacked(firp_ctx* c, const Act& in, const void* w0, int n0, cons
   int n = n0 + n1 + n2;
   if (c->gemm_kind == 1 && gemm_mfma_supported(rows, n, K) && n0 % 4 == 0 && n1 % 4 == 0) {
     Partial out;
-    out.ld = n;
-    out.stride = (size_t)c->Rpad * n;
+    out.ld = n + FIRP_PART_PAD;
+    out.stride = (size_t)c->Rpad * out.ld;
     out.p = c->part;
     GemmPlan plan = gemm_mfma_plan(rows, n, K, 0);
     if ((size_t)plan.S * out.stride > c->part_elems)
@@ -261,7 +265,7 @@ Partial project_stacked(firp_ctx* c, const Act& in, const void* w0, int n0, cons
     bool timed = c->time_gemm && c->ev_used + 2 <= c->ev.size();
     if (timed) (void)hipEventRecord(c->ev[c->ev_used++], c->stream);
     WSeg ws{(const bf16*)w0, (const bf16*)w1, (const bf16*)w2, n0, n1};
-    launch_gemm_mfma(in, ws, c->part, n, out.stride, rows, n, K, plan, c->stream);
+    launch_gemm_mfma(in, ws, c->part, out.ld, out.stride, rows, n, K, plan, c->stream);
     if (timed) {
       (void)hipEventRecord(c->ev[c->ev_used++], c->stream);
       c->gemm_bytes += 2.0 * (double)n * (double)K;
@@ -285,7 +289,7 @@ firp_status forward(firp_ctx* c, int B, int rows_lo, int rows_hi, int n_anchor_r
   RowTab rt = row_tab(c);
   const bool sp = c->split;
   const int qd = d.n_q_heads * d.head_dim, kvd = d.n_kv_heads * d.head_dim;
-  launch_embed(c->embed, c->dtype, c->st.tok, rows_lo, d.d_model, c->x, s);
+  launch_embed(c->embed, c->dtype, c->st.tok, rows_lo, d.d_model, d.vocab, c->x, s);
   launch_rope_table(rt, c->st.p0, rows_hi, d.head_dim, d.rope_base, c->rope_tab, s);
   Partial pending{};  // projection output not yet added to the residual stream
   int pending_rows = 0;

@@ -46,7 +46,7 @@ struct SeqState {
 
 void launch_fill_tokens(const SeqState& st, const TreeTab& tt, int B, const int* injected,
                         hipStream_t s);
-void launch_embed(const void* embed, int dtype, const int* tok, int rows, int d, float* x,
+void launch_embed(const void* embed, int dtype, const int* tok, int rows, int d, int vocab, float* x,
                   hipStream_t s);
 // x[r] += sum of partials (if part.p), then act = rmsnorm(x[r]) * gain.
 void launch_add_rmsnorm(float* x, const Partial& part, int rows, int d, const void* gain,

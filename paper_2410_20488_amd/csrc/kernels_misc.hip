@@ -34,20 +34,20 @@ void launch_fill_tokens(const SeqState& st, const TreeTab& tt, int B, const int*
 
 // ------------------------------------------------------------------------------------------
 template <typename WT>
-__global__ void k_embed(const WT* __restrict__ E, const int* __restrict__ tok, int d, float* x) {
+__global__ void k_embed(const WT* __restrict__ E, const int* __restrict__ tok, int d, int vocab, float* x) {
   int r = blockIdx.x;
   int t = tok[r];
-  if (t < 0) t = 0;
+  if (t < 0 || t >= vocab) t = 0;  // "no candidate" (-1), or an id derived from non-finite logits
   const WT* e = E + (size_t)t * d;
   for (int i = threadIdx.x; i < d; i += blockDim.x) x[(size_t)r * d + i] = to_f32(e[i]);
 }
 
-void launch_embed(const void* embed, int dtype, const int* tok, int rows, int d, float* x,
+void launch_embed(const void* embed, int dtype, const int* tok, int rows, int d, int vocab, float* x,
                   hipStream_t s) {
   if (dtype == DT_BF16)
-    hipLaunchKernelGGL(k_embed<bf16>, dim3(rows), dim3(256), 0, s, (const bf16*)embed, tok, d, x);
+    hipLaunchKernelGGL(k_embed<bf16>, dim3(rows), dim3(256), 0, s, (const bf16*)embed, tok, d, vocab, x);
   else
-    hipLaunchKernelGGL(k_embed<float>, dim3(rows), dim3(256), 0, s, (const float*)embed, tok, d, x);
+    hipLaunchKernelGGL(k_embed<float>, dim3(rows), dim3(256), 0, s, (const float*)embed, tok, d, vocab, x);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -326,6 +326,7 @@ __global__ __launch_bounds__(256) void k_argmax_topb(Partial lg, float* logits_o
     }
     int win = si[0];
     __syncthreads();
+    if (win >= vocab) win = 0;  // only when every remaining logit is NaN
     if (mine[0].id == win) {  // the owner pops its head
 #pragma unroll
       for (int e = 0; e + 1 < BM; ++e) mine[e] = mine[e + 1];
