@@ -1,10 +1,14 @@
 // Tree-masked flash-decode attention for a bf16 KV cache on gfx950 (MFMA 16x16x32 bf16).
 //
-// Grid = (splits over cache length, kv heads, sequences).  A workgroup owns one contiguous
-// chunk of keys of one kv head.  Its work items are "pairs" (16-row tile of the sequence's
-// step rows, q head of the kv group); every wave takes up to two pairs at a time and sweeps
-// the chunk in blocks of 32 keys, reading K and V^T straight from the cache into MFMA operand
-// layout (the waves of a workgroup read the same lines, so HBM sees them once):
+// Grid = (splits over cache length, kv heads, sequences); 8 waves per workgroup, two per SIMD:
+// one wave issues an MFMA at most every 16 cycles and its softmax arithmetic sits between the
+// two products, so a second wave per SIMD is what fills the matrix pipe.  A workgroup owns one
+// contiguous chunk of keys of one kv head and sweeps it in blocks of 32 keys.  Its work items
+// are "pairs" (16-row tile of the sequence's step rows, q head of the kv group), dealt out one
+// per wave first, up to two per wave.  Every block of K and V^T is fetched once per workgroup:
+// each wave loads an eighth of the block's MFMA operand fragments (global -> registers, three
+// blocks ahead), drops them into one of two LDS buffers in the lane order the MFMA wants, and
+// after a barrier every wave reads all fragments back with conflict-free 16-byte LDS reads.
 //   S^T = K . Q^T   A = K block (lane = key, 8 dims), B = Q (lane = row, 8 dims), hi and lo
 //                   planes of Q accumulated into the same tile.  The key <-> MFMA-row map is
 //                   chosen so that a lane ends up with 8 consecutive keys of its row, which is
@@ -17,6 +21,7 @@
 // Each (row, q head, split) leaves (max, sum, unnormalised output); k_attn_combine merges the
 // splits and writes the activation planes for the output projection.
 #include <algorithm>
+#include <type_traits>
 
 #include "kernels.h"
 
@@ -28,10 +33,8 @@ typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
 
 namespace {
 __device__ __forceinline__ bf16x8_t as_bf16x8(u32x4_t v) { return __builtin_bit_cast(bf16x8_t, v); }
-__device__ __forceinline__ unsigned pack_bf16(float a, float b) {
-  return (unsigned)f32_to_bf16(a).v | ((unsigned)f32_to_bf16(b).v << 16);
-}
 constexpr int PAIRS = 2;
+constexpr int NWAVES = 8;
 }  // namespace
 
 // Where the rows of one sequence live in the step's global row order: local id -> row.
@@ -46,39 +49,88 @@ __device__ __forceinline__ int global_row(const SeqRows& sr, int b, int local) {
 }
 
 template <int DH>
-__global__ __launch_bounds__(256, 1) void k_attention_mfma(const bf16* __restrict__ qhi, const bf16* __restrict__ qlo,
+__global__ __launch_bounds__(64 * NWAVES, 1) void k_attention_mfma(const bf16* __restrict__ qhi, const bf16* __restrict__ qlo,
                                                           int ldq, int n_q_heads, SeqRows sr, int n_local,
                                                           const unsigned long long* __restrict__ row_mask,
                                                           const int* __restrict__ p0v, KvView kv, int chunk,
                                                           float* __restrict__ part_o, float* __restrict__ part_ml,
                                                           int splits) {
-  constexpr int DS = DH / 32;  // k-steps of the score product
-  constexpr int DT = DH / 16;  // 16-dim tiles of the output
+  constexpr int DS = DH / 32;       // k-steps of the score product
+  constexpr int DT = DH / 16;       // 16-dim tiles of the output
+  constexpr int NF = 2 * DS + DT;   // operand fragments (64 lanes x 16 B) of one 32-key block
+  constexpr int FPW = (NF + NWAVES - 1) / NWAVES;   // fragments each wave fetches
+  static_assert(NF % NWAVES == 0 || NF < NWAVES, "fragments must divide over the waves");
   const int split = blockIdx.x, hk = blockIdx.y, b = blockIdx.z;
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, n_waves = blockDim.x >> 6;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int r16 = lane & 15, kb = lane >> 4;
   const int G = n_q_heads / kv.n_kv_heads;
   const int n_tiles = (n_local + 15) >> 4;
   const int n_pairs = n_tiles * G;
+  const int key_begin = split * chunk;
+  // last block the launch geometry allows: the first fetches go out against this bound, before
+  // the committed length has even arrived
+  const int hard_last = (min(key_begin + chunk, kv.slots) - key_begin - 32) >> 5;
   const int p0 = p0v[b];
   const int n_keys = p0 + n_local;
-  const int key_begin = split * chunk;
   const int key_end = min(n_keys, key_begin + chunk);
+  const int nb = key_end > key_begin ? (key_end - key_begin + 31) >> 5 : 0;   // blocks of this chunk
+  const int last = nb - 1;
   const bf16* Kb = (const bf16*)kv.k + (size_t)b * kv.seq_stride + (size_t)hk * kv.slots * DH;
   const bf16* Vt = (const bf16*)kv.v + (size_t)b * kv.seq_stride + (size_t)hk * DH * kv.slots;
   const float sc = 1.4426950408889634f / sqrtf((float)DH);  // log2(e) / sqrt(dh)
   const float NEG = -__builtin_inff();
 
-  for (int pp = wave * PAIRS; pp < n_pairs; pp += n_waves * PAIRS) {
-    // ---- this wave's pairs: Q fragments, masks, running state
+  __shared__ u32x4_t kv_lds[2][NF][64];
+  // every row's mask words (two zero words behind them) sit in its wave's corner of LDS, where
+  // the blocks that reach past the committed cache pick the word they need by index
+  __shared__ unsigned long long mk_lds[NWAVES * PAIRS * 16][FIRP_MASK_WORDS + 2];
+
+  // This wave fetches fragments f = NWAVES*j + wave (with fewer fragments than waves, several
+  // waves fetch and store the same one).  Fragments [0, 2*DS) are K: (16-key tile t2,
+  // k-step ds), MFMA row m <-> key 8*(m/4) + (m%4) + 4*t2; the rest are V^T: 16-dim tile dt.
+  // A fragment's address is linear in the block's first key.
+  const char* fbase[FPW];
+  int fstep[FPW];   // bytes per key
+#pragma unroll
+  for (int j = 0; j < FPW; ++j) {
+    const int f = (NWAVES * j + wave) % NF;
+    if (f < 2 * DS) {
+      const int t2 = f / DS, ds = f % DS;
+      fbase[j] = (const char*)(Kb + (size_t)(8 * (r16 >> 2) + (r16 & 3) + 4 * t2) * DH + kb * 8 + ds * 32);
+      fstep[j] = DH * 2;
+    } else {
+      const int dt = f - 2 * DS;
+      fbase[j] = (const char*)(Vt + (size_t)(dt * 16 + r16) * kv.slots + 8 * kb);
+      fstep[j] = 2;
+    }
+  }
+  // every load is unconditional (blocks past the end repeat the last one and are never used) so
+  // that the compiler's wait counters stay exact
+  auto fetch = [&](u32x4_t (&g)[FPW], int blk, int bound) {
+    const size_t key = (size_t)(key_begin + 32 * min(blk, bound));
+#pragma unroll
+    for (int j = 0; j < FPW; ++j) g[j] = *(const u32x4_t*)(fbase[j] + key * fstep[j]);
+  };
+  auto stash = [&](const u32x4_t (&g)[FPW], int buf) {
+#pragma unroll
+    for (int j = 0; j < FPW; ++j) kv_lds[buf][(NWAVES * j + wave) % NF][lane] = g[j];
+  };
+
+  // a sweep covers up to NWAVES * PAIRS pairs: pair `first + wave + NWAVES*p` is this wave's p-th
+  const int n_sweeps = (n_pairs + NWAVES * PAIRS - 1) / (NWAVES * PAIRS);
+  for (int sweep = 0; sweep < n_sweeps; ++sweep) {
+    const int first = sweep * NWAVES * PAIRS;
+    int n_live = 0;
+#pragma unroll
+    for (int p = 0; p < PAIRS; ++p) n_live += first + wave + NWAVES * p < n_pairs;
+    // ---- this wave's pairs: Q fragments, masks, running state.  Q and the masks are cache
+    // hits and are asked for first (loads return in order); the first three K/V blocks follow.
     u32x4_t q[PAIRS][DS][2];
-    unsigned long long mk[PAIRS][FIRP_MASK_WORDS];
+    unsigned long long mw[PAIRS][FIRP_MASK_WORDS];
     int row_of[PAIRS], head_of[PAIRS];
-    bool live[PAIRS];
 #pragma unroll
     for (int p = 0; p < PAIRS; ++p) {
-      int pi = min(pp + p, n_pairs - 1);
-      live[p] = pp + p < n_pairs;
+      int pi = min(first + wave + NWAVES * p, n_pairs - 1);
       int tile = pi / G, g = pi % G;
       int local = min(tile * 16 + r16, n_local - 1);
       int row = global_row(sr, b, local);
@@ -91,7 +143,21 @@ __global__ __launch_bounds__(256, 1) void k_attention_mfma(const bf16* __restric
         q[p][ds][1] = *(const u32x4_t*)(qlo + qoff + ds * 32);
       }
 #pragma unroll
-      for (int wd = 0; wd < FIRP_MASK_WORDS; ++wd) mk[p][wd] = row_mask[(size_t)row * FIRP_MASK_WORDS + wd];
+      for (int wd = 0; wd < FIRP_MASK_WORDS; ++wd) mw[p][wd] = row_mask[(size_t)row * FIRP_MASK_WORDS + wd];
+    }
+    u32x4_t g0[FPW], g1[FPW], g2[FPW];
+    fetch(g0, 0, hard_last);
+    fetch(g1, 1, hard_last);
+    fetch(g2, 2, hard_last);
+    if (kb == 0) {
+#pragma unroll
+      for (int p = 0; p < PAIRS; ++p) {
+        unsigned long long* mrow = mk_lds[(wave * PAIRS + p) * 16 + r16];
+#pragma unroll
+        for (int wd = 0; wd < FIRP_MASK_WORDS; ++wd) mrow[wd] = mw[p][wd];
+        mrow[FIRP_MASK_WORDS] = 0ull;
+        mrow[FIRP_MASK_WORDS + 1] = 0ull;
+      }
     }
     f32x4_t o[PAIRS][DT];
     float m_run[PAIRS], l_run[PAIRS];
@@ -103,105 +169,139 @@ __global__ __launch_bounds__(256, 1) void k_attention_mfma(const bf16* __restric
       for (int dt = 0; dt < DT; ++dt) o[p][dt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
     }
 
-    // ---- sweep the chunk, 32 keys per block
-    auto load_kv = [&](u32x4_t (&kf)[2][DS], u32x4_t (&vf)[DT], int k0) {
-      // K rows of the two 16-key tiles: MFMA row m <-> key 8*(m/4) + (m%4) (+4 for the second)
-      const int key_a = k0 + 8 * (r16 >> 2) + (r16 & 3);
+    // One block of 32 keys against NP pairs, in three phases so that the pairs' independent
+    // MFMA chains and softmax arithmetic interleave: scores, softmax, output.
+    auto block = [&](auto np_tag, int buf, int k0) {
+      constexpr int NP = decltype(np_tag)::value;
+      f32x4_t s[NP][2];
 #pragma unroll
-      for (int t2 = 0; t2 < 2; ++t2) {
-        const bf16* kr = Kb + (size_t)min(key_a + 4 * t2, kv.slots - 1) * DH + kb * 8;
+      for (int p = 0; p < NP; ++p)
 #pragma unroll
-        for (int ds = 0; ds < DS; ++ds) kf[t2][ds] = *(const u32x4_t*)(kr + ds * 32);
-      }
+        for (int t2 = 0; t2 < 2; ++t2) s[p][t2] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-      for (int dt = 0; dt < DT; ++dt) vf[dt] = *(const u32x4_t*)(Vt + (size_t)(dt * 16 + r16) * kv.slots + k0 + 8 * kb);
-    };
-    auto block = [&](u32x4_t (&kf)[2][DS], u32x4_t (&vf)[DT], int k0) {
-      const bool need_mask = k0 + 32 > p0;
-#pragma unroll
-      for (int p = 0; p < PAIRS; ++p) {
-        if (!live[p]) continue;
-        f32x4_t s[2];
+      for (int ds = 0; ds < DS; ++ds)
 #pragma unroll
         for (int t2 = 0; t2 < 2; ++t2) {
-          s[t2] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+          const bf16x8_t kf = as_bf16x8(kv_lds[buf][t2 * DS + ds][lane]);
 #pragma unroll
-          for (int ds = 0; ds < DS; ++ds) {
-            s[t2] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(kf[t2][ds]), as_bf16x8(q[p][ds][0]), s[t2], 0, 0, 0);
-            s[t2] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(kf[t2][ds]), as_bf16x8(q[p][ds][1]), s[t2], 0, 0, 0);
+          for (int p = 0; p < NP; ++p) {
+            s[p][t2] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf, as_bf16x8(q[p][ds][0]), s[p][t2], 0, 0, 0);
+            s[p][t2] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf, as_bf16x8(q[p][ds][1]), s[p][t2], 0, 0, 0);
           }
         }
-        // lane holds scores of row r16 at keys k0 + 8*kb + 4*t2 + i
-        float e[8];
+      // lane holds the raw scores of row r16 at keys k0 + 8*kb + j, j = 4*t2 + i
+      float e[NP][8];
+#pragma unroll
+      for (int p = 0; p < NP; ++p)
 #pragma unroll
         for (int t2 = 0; t2 < 2; ++t2)
 #pragma unroll
-          for (int i = 0; i < 4; ++i) e[t2 * 4 + i] = s[t2][i] * sc;
-        if (need_mask) {
+          for (int i = 0; i < 4; ++i) e[p][t2 * 4 + i] = s[p][t2][i];
+      if (k0 + 32 > p0) {
+        // bit j of `vis`: key k0 + 8*kb + j is visible to this lane's row
+        const int c0 = k0 + 8 * kb - p0;  // step-local index of the lane's first key
 #pragma unroll
-          for (int j = 0; j < 8; ++j) {
-            int key = k0 + 8 * kb + j;
-            int c = key - p0;
-            int wd = c >> 6;
-            unsigned long long word = wd == 0 ? mk[p][0] : wd == 1 ? mk[p][1] : wd == 2 ? mk[p][2] : mk[p][3];
-            bool vis = key < p0 || (c < n_local && ((word >> (c & 63)) & 1ull));
-            e[j] = vis ? e[j] : NEG;
+        for (int p = 0; p < NP; ++p) {
+          const unsigned long long* mrow = mk_lds[(wave * PAIRS + p) * 16 + r16];
+          unsigned vis;
+          if (c0 <= -8) {
+            vis = 0xffu;
+          } else if (c0 < 0) {
+            vis = (unsigned)(mrow[0] << (-c0)) | ((1u << (-c0)) - 1u);
+          } else {
+            const int wd = min(c0 >> 6, FIRP_MASK_WORDS), sh = c0 & 63;
+            vis = (unsigned)(mrow[wd] >> sh);
+            if (sh > 56) vis |= (unsigned)(mrow[wd + 1] << (64 - sh));
           }
-        }
-        float mx = e[0];
 #pragma unroll
-        for (int j = 1; j < 8; ++j) mx = fmaxf(mx, e[j]);
-        mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
-        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-        float m_new = fmaxf(m_run[p], mx);
-        float m_use = (m_new == NEG) ? 0.f : m_new;
-        float alpha = exp2f(m_run[p] - m_use);
-        m_run[p] = m_new;
+          for (int j = 0; j < 8; ++j) e[p][j] = ((vis >> j) & 1u) ? e[p][j] : NEG;
+        }
+      }
+      float mx[NP];
+#pragma unroll
+      for (int p = 0; p < NP; ++p)
+        mx[p] = fmaxf(fmaxf(fmaxf(e[p][0], e[p][1]), fmaxf(e[p][2], e[p][3])),
+                      fmaxf(fmaxf(e[p][4], e[p][5]), fmaxf(e[p][6], e[p][7])));
+#pragma unroll
+      for (int p = 0; p < NP; ++p) mx[p] = fmaxf(mx[p], __shfl_xor(mx[p], 16, 64));
+#pragma unroll
+      for (int p = 0; p < NP; ++p) mx[p] = fmaxf(mx[p], __shfl_xor(mx[p], 32, 64)) * sc;
+      // The reference point m_run of the exponentials only has to stay within 2^8 of the true
+      // running maximum (any reference gives the same quotient in the end), so the rescale of
+      // the accumulators is taken only when some row of a tile moved further than that.
+      bool moved = false;   // stays false for a row with nothing visible yet
+#pragma unroll
+      for (int p = 0; p < NP; ++p) moved |= mx[p] > m_run[p] + 8.0f;
+      if (__builtin_amdgcn_ballot_w64(moved) != 0ull) {
+#pragma unroll
+        for (int p = 0; p < NP; ++p) {
+          const float m_new = fmaxf(m_run[p], mx[p]);
+          const float alpha = (m_new == NEG) ? 1.0f : __builtin_amdgcn_exp2f(m_run[p] - m_new);
+          m_run[p] = m_new;
+          l_run[p] *= alpha;
+#pragma unroll
+          for (int dt = 0; dt < DT; ++dt) o[p][dt] *= alpha;
+        }
+      }
+      // probabilities as two bf16 planes (hi + lo), like every other MFMA activation operand
+      u32x4_t pf[NP], pw[NP];
+#pragma unroll
+      for (int p = 0; p < NP; ++p) {
+        const float nm = (m_run[p] == NEG) ? 0.f : -m_run[p];
         float psum = 0.f;
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
-          e[j] = exp2f(e[j] - m_use);
-          psum += e[j];
+          e[p][j] = __builtin_amdgcn_exp2f(__builtin_fmaf(e[p][j], sc, nm));
+          psum += e[p][j];
         }
-        l_run[p] = l_run[p] * alpha + psum;
-        // probabilities as two bf16 planes (hi + lo), like every other MFMA activation operand
-        float eh[8];
+        l_run[p] += psum;
+        unsigned h[4], l[4];
 #pragma unroll
-        for (int j = 0; j < 8; ++j) eh[j] = to_f32(f32_to_bf16(e[j]));
-        u32x4_t pf, pl;
-        pf.x = pack_bf16(eh[0], eh[1]);
-        pf.y = pack_bf16(eh[2], eh[3]);
-        pf.z = pack_bf16(eh[4], eh[5]);
-        pf.w = pack_bf16(eh[6], eh[7]);
-        pl.x = pack_bf16(e[0] - eh[0], e[1] - eh[1]);
-        pl.y = pack_bf16(e[2] - eh[2], e[3] - eh[3]);
-        pl.z = pack_bf16(e[4] - eh[4], e[5] - eh[5]);
-        pl.w = pack_bf16(e[6] - eh[6], e[7] - eh[7]);
+        for (int j = 0; j < 4; ++j) split2_bf16(e[p][2 * j], e[p][2 * j + 1], h[j], l[j]);
+        pf[p] = u32x4_t{h[0], h[1], h[2], h[3]};
+        pw[p] = u32x4_t{l[0], l[1], l[2], l[3]};
+      }
 #pragma unroll
-        for (int dt = 0; dt < DT; ++dt) {
-          o[p][dt] *= alpha;
-          o[p][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(vf[dt]), as_bf16x8(pf), o[p][dt], 0, 0, 0);
-          o[p][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(vf[dt]), as_bf16x8(pl), o[p][dt], 0, 0, 0);
+      for (int dt = 0; dt < DT; ++dt) {
+        const bf16x8_t vf = as_bf16x8(kv_lds[buf][2 * DS + dt][lane]);
+#pragma unroll
+        for (int p = 0; p < NP; ++p) {
+          o[p][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, as_bf16x8(pf[p]), o[p][dt], 0, 0, 0);
+          o[p][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, as_bf16x8(pw[p]), o[p][dt], 0, 0, 0);
         }
       }
     };
-    // two register sets: the loads of block i+1 are in flight while block i is multiplied
-    u32x4_t kfa[2][DS], vfa[DT], kfb[2][DS], vfb[DT];
-    const int k_last = max(key_begin, ((key_end - 1) >> 5) << 5);   // start of the last block
-    if (key_begin < key_end) load_kv(kfa, vfa, key_begin);
-    int k0 = key_begin;
-    for (; k0 + 32 < key_end; k0 += 64) {
-      load_kv(kfb, vfb, k0 + 32);
-      block(kfa, vfa, k0);
-      load_kv(kfa, vfa, min(k0 + 64, k_last));
-      block(kfb, vfb, k0 + 32);
+    // ---- sweep the chunk.  Step i: barrier (block i is in LDS buffer i&1 and nobody still
+    // reads the other buffer), multiply block i, then move block i+1 from its register set to
+    // the other buffer and send that set for block i+4.
+    auto step = [&](u32x4_t (&gnext)[FPW], int i) {
+      __syncthreads();
+      const int k0 = key_begin + 32 * i;
+      if (n_live == PAIRS)
+        block(std::integral_constant<int, PAIRS>{}, i & 1, k0);
+      else if (n_live == 1)
+        block(std::integral_constant<int, 1>{}, i & 1, k0);
+      stash(gnext, (i + 1) & 1);
+      fetch(gnext, i + 4, last);
+    };
+    if (nb > 0) {
+      stash(g0, 0);
+      fetch(g0, 3, last);
+      int i = 0;
+      for (; i + 3 <= nb; i += 3) {
+        step(g1, i);
+        step(g2, i + 1);
+        step(g0, i + 2);
+      }
+      if (i < nb) step(g1, i);
+      if (i + 1 < nb) step(g2, i + 1);
     }
-    if (k0 < key_end) block(kfa, vfa, k0);
+    __syncthreads();   // the next sweep overwrites both buffers
 
     // ---- leave this split's partial result: lane holds O[row r16][dim dt*16 + 4*kb + i]
 #pragma unroll
     for (int p = 0; p < PAIRS; ++p) {
-      if (!live[p] || row_of[p] < 0) continue;
+      if (p >= n_live || row_of[p] < 0) continue;
       float l = l_run[p];
       l += __shfl_xor(l, 16, 64);
       l += __shfl_xor(l, 32, 64);
@@ -264,12 +364,9 @@ void launch_attention_mfma(const Act& q, int rows, int n_q_heads, int B, int n_r
   int splits = std::max(1, std::min({want, blocks, FIRP_ATTN_MAX_SPLITS}));
   int chunk = ((blocks + splits - 1) / splits) * 32;
   splits = (n_keys + chunk - 1) / chunk;
-  const int G = n_q_heads / kv.n_kv_heads;
-  int n_pairs = ((n_local + 15) / 16) * G;
-  int n_waves = std::max(1, std::min(4, (n_pairs + PAIRS - 1) / PAIRS));
   float* part_o = scratch;
   float* part_ml = scratch + (size_t)rows * n_q_heads * FIRP_ATTN_MAX_SPLITS * dh;
-  dim3 g(splits, kv.n_kv_heads, B), blk(64 * n_waves);
+  dim3 g(splits, kv.n_kv_heads, B), blk(64 * NWAVES);
   if (dh == 128)
     hipLaunchKernelGGL(k_attention_mfma<128>, g, blk, 0, s, q.hi, q.lo, q.ld, n_q_heads, sr, n_local, rt.mask, p0, kv, chunk, part_o, part_ml, splits);
   else if (dh == 64)

@@ -13,17 +13,23 @@ struct bf16 {
 __device__ __forceinline__ float to_f32(float x) { return x; }
 __device__ __forceinline__ float to_f32(bf16 x) { return __uint_as_float(((unsigned)x.v) << 16); }
 
-// round-to-nearest-even fp32 -> bf16 (NaN stays NaN)
+// round-to-nearest-even fp32 -> bf16 with the hardware conversion (v_cvt_pk_bf16_f32)
+typedef __bf16 bf16x2_hw __attribute__((ext_vector_type(2)));
+typedef float f32x2_hw __attribute__((ext_vector_type(2)));
 __device__ __forceinline__ bf16 f32_to_bf16(float f) {
-  unsigned u = __float_as_uint(f);
   bf16 r;
-  if ((u & 0x7fffffffu) > 0x7f800000u) {
-    r.v = (unsigned short)((u >> 16) | 0x40);
-  } else {
-    u += 0x7fffu + ((u >> 16) & 1u);
-    r.v = (unsigned short)(u >> 16);
-  }
+  r.v = __builtin_bit_cast(unsigned short, (__bf16)f);
   return r;
+}
+// two values -> one 32-bit word, `a` in the low half
+__device__ __forceinline__ unsigned pack2_bf16(float a, float b) {
+  f32x2_hw v = {a, b};
+  return __builtin_bit_cast(unsigned, __builtin_convertvector(v, bf16x2_hw));
+}
+// hi/lo planes of two values: hi = rne(v), lo = rne(v - hi)
+__device__ __forceinline__ void split2_bf16(float a, float b, unsigned& hi, unsigned& lo) {
+  hi = pack2_bf16(a, b);
+  lo = pack2_bf16(a - __uint_as_float(hi << 16), b - __uint_as_float(hi & 0xffff0000u));
 }
 
 template <typename T>
@@ -59,14 +65,9 @@ __device__ __forceinline__ void act_store(const Act& a, size_t idx, float v) {
 template <bool SPLIT>
 __device__ __forceinline__ void act_store4(const Act& a, size_t idx, float v0, float v1, float v2, float v3) {
   if constexpr (SPLIT) {
-    bf16 h0 = f32_to_bf16(v0), h1 = f32_to_bf16(v1), h2 = f32_to_bf16(v2), h3 = f32_to_bf16(v3);
-    bf16 l0 = f32_to_bf16(v0 - to_f32(h0)), l1 = f32_to_bf16(v1 - to_f32(h1));
-    bf16 l2 = f32_to_bf16(v2 - to_f32(h2)), l3 = f32_to_bf16(v3 - to_f32(h3));
     uint2 ph, pl;
-    ph.x = (unsigned)h0.v | ((unsigned)h1.v << 16);
-    ph.y = (unsigned)h2.v | ((unsigned)h3.v << 16);
-    pl.x = (unsigned)l0.v | ((unsigned)l1.v << 16);
-    pl.y = (unsigned)l2.v | ((unsigned)l3.v << 16);
+    split2_bf16(v0, v1, ph.x, pl.x);
+    split2_bf16(v2, v3, ph.y, pl.y);
     *(uint2*)(a.hi + idx) = ph;
     *(uint2*)(a.lo + idx) = pl;
   } else {
