@@ -69,6 +69,14 @@ int main(int argc, char** argv) {
     unsigned short* pool;
     CK(hipMalloc(&pool, wbytes * cnt));
     hipLaunchKernelGGL(k_fill_bf16, dim3(8192), dim3(256), 0, 0, pool, wbytes * cnt / 2, 17u);
+    // the kernel streams the fragment-major copies
+    const size_t pbytes = gemm_packed_bytes(sh.n, sh.K);
+    char* packed;
+    CK(hipMalloc(&packed, pbytes * cnt));
+    for (int i = 0; i < cnt; ++i)
+      launch_pack_weights(wseg1(pool + (size_t)i * (wbytes / 2), sh.n), sh.n, sh.K, packed + (size_t)i * pbytes, 0);
+    CK(hipDeviceSynchronize());
+    CK(hipFree(pool));
     int rp = (rows + 15) / 16 * 16;
     unsigned short *xh, *xl;
     CK(hipMalloc(&xh, (size_t)rp * sh.K * 2));
@@ -83,7 +91,7 @@ int main(int argc, char** argv) {
     a.lo = (bf16*)xl;
     a.ld = sh.K;
     auto run = [&](int i) {
-      launch_gemm_mfma(a, wseg1(pool + (size_t)(i % cnt) * (wbytes / 2), sh.n), part, sh.n, (size_t)rp * sh.n, rows, sh.n, sh.K, plan, 0);
+      launch_gemm_mfma(a, packed + (size_t)(i % cnt) * pbytes, part, sh.n, (size_t)rp * sh.n, rows, sh.n, sh.K, plan, 0);
     };
     for (int i = 0; i < cnt; ++i) run(i);
     CK(hipDeviceSynchronize());
@@ -98,7 +106,7 @@ int main(int argc, char** argv) {
     printf("rows %3d n %6d K %6d  splits %2d waves/wg %d grid %3d : %7.1f us/launch  %6.0f GB/s of weights  (%.1f MB/launch)\n",
            rows, sh.n, sh.K, plan.S, plan.nw, plan.grid, us, wbytes / us / 1e3, wbytes / 1e6);
     fflush(stdout);
-    CK(hipFree(pool));
+    CK(hipFree(packed));
     CK(hipFree(xh));
     CK(hipFree(xl));
     CK(hipFree(part));

@@ -62,6 +62,11 @@ struct firp_ctx {
   const void* norm_final = nullptr;
   const void* lm_head = nullptr;
   std::vector<const void*> wq, wk, wv, wo, wg, wu, wd, n1, n2, pw, pb;
+  // fragment-major copies of the projection matrices (bf16 models; see gemm_packed_bytes):
+  // q|k|v and gate|up stacked along n, made on the stream by the first prefill
+  std::vector<void*> pk_qkv, pk_o, pk_gu, pk_d, pk_proj;
+  void* pk_head = nullptr;
+  bool packed = false;
   // geometry
   int Rmax = 0, Rpad = 0, slots = 0, qkv_ld = 0, esize = 0;
   size_t kv_layer_stride = 0, kv_seq_stride = 0;
@@ -152,6 +157,22 @@ size_t carve(firp_ctx* c, char* base) {
   act(c->act_o, qd);
   act(c->act_f, d.d_ffn);
   act(c->act_p, d.d_model);
+  if (c->dtype == FIRP_BF16) {
+    auto pk = [&](int n, int K) { return (void*)cv.take<char>(gemm_packed_bytes(n, K)); };
+    c->pk_qkv.assign(d.n_layers, nullptr);
+    c->pk_o.assign(d.n_layers, nullptr);
+    c->pk_gu.assign(d.n_layers, nullptr);
+    c->pk_d.assign(d.n_layers, nullptr);
+    c->pk_proj.assign(c->k, nullptr);
+    for (int i = 0; i < d.n_layers; ++i) {
+      c->pk_qkv[i] = pk(c->qkv_ld, d.d_model);
+      c->pk_o[i] = pk(d.d_model, qd);
+      c->pk_gu[i] = pk(2 * d.d_ffn, d.d_model);
+      c->pk_d[i] = pk(d.d_model, d.d_ffn);
+    }
+    for (int i = 0; i < c->k; ++i) c->pk_proj[i] = pk(d.d_model, d.d_model);
+    c->pk_head = pk(d.vocab, d.d_model);
+  }
   size_t kv_elems = (size_t)d.max_batch * c->kv_seq_stride;
   c->kcache = cv.take<char>(kv_elems * es);
   c->vcache = cv.take<char>(kv_elems * es);
@@ -223,19 +244,19 @@ TreeTab tree_tab(const firp_ctx* c, int N, int P) {
 
 // y = act . W^T into the partial-sum buffer at column `col` of rows that are `ld` wide.
 // `like`: an earlier projection into the same rows whose split factor must be matched.
-Partial project(firp_ctx* c, const Act& in, const void* w, int rows, int n, int K, int ld, int col,
-                const Partial* like) {
+Partial project(firp_ctx* c, const Act& in, const void* w, const void* w_packed, int rows, int n, int K, int ld,
+                int col, const Partial* like) {
   Partial out;
   out.ld = ld + FIRP_PART_PAD;
   out.stride = (size_t)c->Rpad * out.ld;
   out.p = c->part;
-  if (c->gemm_kind == 1 && gemm_mfma_supported(rows, n, K)) {
+  if (c->gemm_kind == 1 && w_packed && gemm_mfma_supported(rows, n, K)) {
     GemmPlan plan = gemm_mfma_plan(rows, n, K, like ? like->S : 0);
     if ((size_t)plan.S * out.stride > c->part_elems)  // never outgrow the partial-sum buffer
       plan = gemm_mfma_plan(rows, n, K, (int)std::max<size_t>(1, c->part_elems / out.stride));
     bool timed = c->time_gemm && c->ev_used + 2 <= c->ev.size();
     if (timed) (void)hipEventRecord(c->ev[c->ev_used++], c->stream);
-    launch_gemm_mfma(in, wseg1(w, n), c->part + col, out.ld, out.stride, rows, n, K, plan, c->stream);
+    launch_gemm_mfma(in, w_packed, c->part + col, out.ld, out.stride, rows, n, K, plan, c->stream);
     if (timed) {
       (void)hipEventRecord(c->ev[c->ev_used++], c->stream);
       c->gemm_bytes += 2.0 * (double)n * (double)K;
@@ -252,9 +273,9 @@ Partial project(firp_ctx* c, const Act& in, const void* w, int rows, int n, int 
 // Up to three matrices sharing the input, written side by side (q|k|v, gate|up): one launch of
 // the MFMA kernel, or one plain launch per matrix.
 Partial project_stacked(firp_ctx* c, const Act& in, const void* w0, int n0, const void* w1, int n1,
-                        const void* w2, int n2, int rows, int K) {
+                        const void* w2, int n2, const void* w_packed, int rows, int K) {
   int n = n0 + n1 + n2;
-  if (c->gemm_kind == 1 && gemm_mfma_supported(rows, n, K) && n0 % 4 == 0 && n1 % 4 == 0) {
+  if (c->gemm_kind == 1 && w_packed && gemm_mfma_supported(rows, n, K)) {
     Partial out;
     out.ld = n + FIRP_PART_PAD;
     out.stride = (size_t)c->Rpad * out.ld;
@@ -264,8 +285,7 @@ Partial project_stacked(firp_ctx* c, const Act& in, const void* w0, int n0, cons
       plan = gemm_mfma_plan(rows, n, K, (int)std::max<size_t>(1, c->part_elems / out.stride));
     bool timed = c->time_gemm && c->ev_used + 2 <= c->ev.size();
     if (timed) (void)hipEventRecord(c->ev[c->ev_used++], c->stream);
-    WSeg ws{(const bf16*)w0, (const bf16*)w1, (const bf16*)w2, n0, n1};
-    launch_gemm_mfma(in, ws, c->part, out.ld, out.stride, rows, n, K, plan, c->stream);
+    launch_gemm_mfma(in, w_packed, c->part, out.ld, out.stride, rows, n, K, plan, c->stream);
     if (timed) {
       (void)hipEventRecord(c->ev[c->ev_used++], c->stream);
       c->gemm_bytes += 2.0 * (double)n * (double)K;
@@ -274,16 +294,44 @@ Partial project_stacked(firp_ctx* c, const Act& in, const void* w0, int n0, cons
     out.S = plan.S;
     return out;
   }
-  Partial q = project(c, in, w0, rows, n0, K, n, 0, nullptr);
-  project(c, in, w1, rows, n1, K, n, n0, &q);
-  if (n2 > 0) project(c, in, w2, rows, n2, K, n, n0 + n1, &q);
+  Partial q = project(c, in, w0, nullptr, rows, n0, K, n, 0, nullptr);
+  project(c, in, w1, nullptr, rows, n1, K, n, n0, &q);
+  if (n2 > 0) project(c, in, w2, nullptr, rows, n2, K, n, n0 + n1, &q);
   return q;
+}
+
+// Every projection shape of the model is one the MFMA kernel takes.
+bool mfma_shapes_ok(const firp_model_desc& d, int qkv_ld) {
+  const int qd = d.n_q_heads * d.head_dim;
+  return gemm_mfma_supported(1, qkv_ld, d.d_model) && gemm_mfma_supported(1, d.d_model, qd) &&
+         gemm_mfma_supported(1, 2 * d.d_ffn, d.d_model) && gemm_mfma_supported(1, d.d_model, d.d_ffn) &&
+         gemm_mfma_supported(1, d.vocab, d.d_model);
+}
+
+// Make the fragment-major copies of the projection matrices (once, on the library's stream).
+void ensure_packed(firp_ctx* c) {
+  if (c->packed || c->dtype != FIRP_BF16 || c->pk_qkv.empty()) return;
+  const firp_model_desc& d = c->d;
+  const int qd = d.n_q_heads * d.head_dim, kvd = d.n_kv_heads * d.head_dim;
+  hipStream_t s = c->stream;
+  for (int i = 0; i < d.n_layers; ++i) {
+    launch_pack_weights(WSeg{(const bf16*)c->wq[i], (const bf16*)c->wk[i], (const bf16*)c->wv[i], qd, kvd},
+                        c->qkv_ld, d.d_model, c->pk_qkv[i], s);
+    launch_pack_weights(wseg1(c->wo[i], d.d_model), d.d_model, qd, c->pk_o[i], s);
+    launch_pack_weights(WSeg{(const bf16*)c->wg[i], (const bf16*)c->wu[i], nullptr, d.d_ffn, d.d_ffn},
+                        2 * d.d_ffn, d.d_model, c->pk_gu[i], s);
+    launch_pack_weights(wseg1(c->wd[i], d.d_model), d.d_model, d.d_ffn, c->pk_d[i], s);
+  }
+  for (int i = 0; i < c->k; ++i) launch_pack_weights(wseg1(c->pw[i], d.d_model), d.d_model, d.d_model, c->pk_proj[i], s);
+  launch_pack_weights(wseg1(c->lm_head, d.vocab), d.vocab, d.d_model, c->pk_head, s);
+  c->packed = true;
 }
 
 // The decoder over `rows_lo` rows for layers < l and `rows_hi` rows from layer l on.  With
 // `head`, ends with final norm, lm-head and argmax / top-b.
 firp_status forward(firp_ctx* c, int B, int rows_lo, int rows_hi, int n_anchor_rows, int n_local_lo,
                     int n_local_hi, int real_rows, bool head, int max_ctx_now) {
+  if (c->gemm_kind == 1) ensure_packed(c);
   const firp_model_desc& d = c->d;
   hipStream_t s = c->stream;
   RowTab rt = row_tab(c);
@@ -302,7 +350,8 @@ firp_status forward(firp_ctx* c, int B, int rows_lo, int rows_hi, int n_anchor_r
       pending = Partial{};
       launch_gather_rows(c->x, c->pseudo_src, n_anchor_rows, d.d_model, c->act_p, sp, s);
       for (int i = 0; i < c->k; ++i) {
-        Partial y = project(c, c->act_p, c->pw[i], n_anchor_rows, d.d_model, d.d_model, d.d_model, 0, nullptr);
+        Partial y = project(c, c->act_p, c->pw[i], c->packed ? c->pk_proj[i] : nullptr, n_anchor_rows, d.d_model,
+                            d.d_model, d.d_model, 0, nullptr);
         launch_scatter_pseudo(y, n_anchor_rows, d.d_model, c->k, i, c->pb.empty() ? nullptr : c->pb[i],
                               c->dtype, c->x, rows_lo, s);
       }
@@ -313,7 +362,8 @@ firp_status forward(firp_ctx* c, int B, int rows_lo, int rows_hi, int n_anchor_r
         break;
       }
       launch_add_rmsnorm(c->x, pending, rows, d.d_model, c->norm_final, c->dtype, d.rms_eps, c->act_d, sp, s);
-      Partial lg = project(c, c->act_d, c->lm_head, rows, d.vocab, d.d_model, d.vocab, 0, nullptr);
+      Partial lg = project(c, c->act_d, c->lm_head, c->packed ? c->pk_head : nullptr, rows, d.vocab, d.d_model,
+                           d.vocab, 0, nullptr);
       launch_argmax_topb(lg, c->logits, real_rows, rows, d.vocab, d.b_max, c->st.amax, c->st.top, s);
       break;
     }
@@ -323,7 +373,8 @@ firp_status forward(firp_ctx* c, int B, int rows_lo, int rows_hi, int n_anchor_r
       pending = Partial{};
     }
     launch_add_rmsnorm(c->x, pending, rows, d.d_model, c->n1[layer], c->dtype, d.rms_eps, c->act_d, sp, s);
-    Partial q = project_stacked(c, c->act_d, c->wq[layer], qd, c->wk[layer], kvd, c->wv[layer], kvd, rows, d.d_model);
+    Partial q = project_stacked(c, c->act_d, c->wq[layer], qd, c->wk[layer], kvd, c->wv[layer], kvd,
+                                c->packed ? c->pk_qkv[layer] : nullptr, rows, d.d_model);
     KvView kv = kv_view(c, layer);
     launch_rope_kv(q, rows, d.n_q_heads, rt, c->st.p0, c->rope_tab, c->act_q, sp, kv, c->dtype, s);
     if (c->attn_kind == 1 && sp)
@@ -332,11 +383,14 @@ firp_status forward(firp_ctx* c, int B, int rows_lo, int rows_hi, int n_anchor_r
     else
       launch_attention_simple(c->act_q, sp, rows, d.n_q_heads, rt, c->st.p0, kv, c->dtype, c->act_o, n_local,
                               max_ctx_now + n_local, s);
-    Partial o = project(c, c->act_o, c->wo[layer], rows, d.d_model, qd, d.d_model, 0, nullptr);
+    Partial o = project(c, c->act_o, c->wo[layer], c->packed ? c->pk_o[layer] : nullptr, rows, d.d_model, qd,
+                        d.d_model, 0, nullptr);
     launch_add_rmsnorm(c->x, o, rows, d.d_model, c->n2[layer], c->dtype, d.rms_eps, c->act_d, sp, s);
-    Partial g = project_stacked(c, c->act_d, c->wg[layer], d.d_ffn, c->wu[layer], d.d_ffn, nullptr, 0, rows, d.d_model);
+    Partial g = project_stacked(c, c->act_d, c->wg[layer], d.d_ffn, c->wu[layer], d.d_ffn, nullptr, 0,
+                                c->packed ? c->pk_gu[layer] : nullptr, rows, d.d_model);
     launch_swiglu(g, rows, d.d_ffn, c->act_f, sp, s);
-    pending = project(c, c->act_f, c->wd[layer], rows, d.d_model, d.d_ffn, d.d_model, 0, nullptr);
+    pending = project(c, c->act_f, c->wd[layer], c->packed ? c->pk_d[layer] : nullptr, rows, d.d_model, d.d_ffn,
+                      d.d_model, 0, nullptr);
     pending_rows = rows;
   }
   hipError_t e = hipGetLastError();
@@ -587,7 +641,8 @@ firp_status firp_init(firp_ctx** out, const firp_model_desc* desc, const firp_we
     c->pw.assign(proj_w, proj_w + k);
     if (proj_b) c->pb.assign(proj_b, proj_b + k);
   }
-  c->gemm_kind = desc->dtype == FIRP_BF16 ? 1 : 0;  // bf16 models stream weights through MFMA
+  // bf16 models stream weights through MFMA (when every projection shape fits the kernel)
+  c->gemm_kind = (desc->dtype == FIRP_BF16 && mfma_shapes_ok(*desc, c->qkv_ld)) ? 1 : 0;
   c->split = c->gemm_kind == 1;
   c->attn_kind = (c->split && attention_mfma_supported(desc->head_dim, desc->dtype)) ? 1 : 0;
   c->p0.assign(desc->max_batch, 0);
@@ -812,7 +867,7 @@ firp_status firp_set_option(firp_ctx* c, const char* name, int32_t value) {
       c->attn_kind = 0;
       return FIRP_OK;
     }
-    if (value == 1 && c->dtype == FIRP_BF16) {
+    if (value == 1 && c->dtype == FIRP_BF16 && mfma_shapes_ok(c->d, c->qkv_ld)) {
       c->gemm_kind = 1;
       c->split = true;
       c->attn_kind = attention_mfma_supported(c->d.head_dim, c->dtype) ? 1 : 0;
@@ -861,7 +916,9 @@ firp_status firp_get_gemm_timing(const firp_ctx* c, int64_t* launches, double* t
 size_t firp_gemm_workspace_bytes(int32_t rows, int32_t n, int32_t k_dim) {
   if (rows < 1 || n < 1 || k_dim < 1) return 0;
   size_t rp = align_up(rows, 16);
-  return align_up(rp * k_dim * 2 * 2, 256) + align_up(rp * (size_t)n * 4 * 8, 256) + 512;
+  // activation planes, partial sums of up to 16 splits, the fragment-major copy of W
+  return align_up(rp * k_dim * 2 * 2, 256) + align_up(rp * (size_t)n * 4 * 16, 256) +
+         align_up(gemm_packed_bytes(n, k_dim), 256) + 512;
 }
 
 firp_status firp_debug_gemm(const float* x, const void* w, float* y, int32_t rows, int32_t n, int32_t k_dim,
@@ -882,9 +939,11 @@ firp_status firp_debug_gemm(const float* x, const void* w, float* y, int32_t row
     a.hi = (bf16*)workspace;
     a.lo = a.hi + rp * k_dim;
     float* part = (float*)((char*)workspace + align_up(rp * k_dim * 2 * 2, 256));
+    void* wpk = (char*)part + align_up(rp * (size_t)n * 4 * 16, 256);
     launch_split_act(x, rows, k_dim, a, s);
+    launch_pack_weights(wseg1(w, n), n, k_dim, wpk, s);
     GemmPlan plan = gemm_mfma_plan(rows, n, k_dim, 0);
-    launch_gemm_mfma(a, wseg1(w, n), part, n, rp * n, rows, n, k_dim, plan, s);
+    launch_gemm_mfma(a, wpk, part, n, rp * n, rows, n, k_dim, plan, s);
     launch_reduce_partials(Partial{part, plan.S, rp * (size_t)n, n}, y, rows, s);
   } else {
     return FIRP_EINVAL;

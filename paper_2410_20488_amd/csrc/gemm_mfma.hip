@@ -61,7 +61,44 @@ GemmPlan gemm_mfma_plan(int rows, int n, int K, int force_split) {
   return gemm_mfma_plan_ex(rows, n, K, best_S, best_nw);
 }
 
-void launch_gemm_mfma(const Act& x, const WSeg& w, float* out, int ld, size_t part_stride, int rows, int n,
+size_t gemm_packed_bytes(int n, int K) {
+  return (size_t)((n + 15) / 16) * (size_t)(((K + KC - 1) / KC) * 2) * 1024;
+}
+
+// One thread per 16-byte piece of the fragment-major copy.
+__global__ void k_pack_weights(WSeg src, int n, int K, int kp32, size_t pieces, uint4* __restrict__ dst) {
+  size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= pieces) return;
+  const int lane = (int)(idx & 63);
+  const size_t frag = idx >> 6;
+  const int t16 = (int)(frag / kp32), ks = (int)(frag % kp32);
+  const int row = t16 * 16 + (lane & 15), k = ks * 32 + (lane >> 4) * 8;
+  union {
+    uint4 v;
+    unsigned short e[8];
+  } u;
+  u.v = make_uint4(0, 0, 0, 0);
+  if (row < n && k < K) {
+    const bf16* r = row < src.n0 ? src.w0 + (size_t)row * K
+                    : row < src.n0 + src.n1 ? src.w1 + (size_t)(row - src.n0) * K
+                                            : src.w2 + (size_t)(row - src.n0 - src.n1) * K;
+    if (k + 8 <= K && (K & 7) == 0) {
+      u.v = *(const uint4*)(r + k);
+    } else {
+      for (int i = 0; i < 8 && k + i < K; ++i) u.e[i] = r[k + i].v;
+    }
+  }
+  dst[idx] = u.v;
+}
+
+void launch_pack_weights(const WSeg& src, int n, int K, void* dst, hipStream_t s) {
+  const int kp32 = ((K + KC - 1) / KC) * 2;
+  const size_t pieces = gemm_packed_bytes(n, K) / 16;
+  const unsigned blocks = (unsigned)((pieces + 255) / 256);
+  hipLaunchKernelGGL(k_pack_weights, dim3(blocks), dim3(256), 0, s, src, n, K, kp32, pieces, (uint4*)dst);
+}
+
+void launch_gemm_mfma(const Act& x, const void* w_packed, float* out, int ld, size_t part_stride, int rows, int n,
                       int K, const GemmPlan& plan, hipStream_t s) {
   // more than 128 rows: row blocks of 128 (W is streamed once per block)
   for (int r0 = 0; r0 < rows; r0 += 128) {
@@ -71,6 +108,7 @@ void launch_gemm_mfma(const Act& x, const WSeg& w, float* out, int ld, size_t pa
     const bf16* xhi = x.hi + (size_t)r0 * x.ld;
     const bf16* xlo = x.lo + (size_t)r0 * x.ld;
     float* o = out + (size_t)r0 * ld;
+    const char* w = (const char*)w_packed;
     switch (p.nw) {
       case 2: launch_gemm_mfma_nw<2>(xhi, xlo, x.ld, rb, w, n, K, o, ld, part_stride, p, s); break;
       case 3: launch_gemm_mfma_nw<3>(xhi, xlo, x.ld, rb, w, n, K, o, ld, part_stride, p, s); break;

@@ -4,9 +4,12 @@
 //
 // The step is bound by streaming W from HBM once, so the kernel is built around that stream:
 //  * every wave owns 16*MT rows of W and reads them straight from global memory into the
-//    A-operand layout of v_mfma_f32_16x16x32_bf16 (lane = (row % 16, k-block of 8)): four lanes
-//    cover 64 contiguous bytes of a row and two loads cover a 128-byte line; loads for the
-//    stage after next are in flight while the current one is multiplied;
+//    A-operand layout of v_mfma_f32_16x16x32_bf16 (lane = (row % 16, k-block of 8)).  W is kept
+//    in a fragment-major copy made once (see gemm_packed_bytes): a load instruction then covers
+//    1 KiB of contiguous memory, eight whole cache lines, instead of 64-byte halves of sixteen
+//    lines that a second instruction touches again while they are still on their way - the
+//    vector cache tracks few outstanding lines per CU and stalls on exactly that pattern.
+//    Loads for three stages ahead are in flight while the current one is multiplied;
 //  * the activations are the small operand: a stage's [16*NT rows][64 k] tile of both planes
 //    (hi and lo bf16, see Act) is staged once per workgroup through LDS (double-buffered, row
 //    pitch 144 B so that 128-bit reads of 8 consecutive rows hit distinct banks) and shared by
@@ -36,7 +39,7 @@ __device__ __forceinline__ bf16x8_t as_bf16x8(u32x4_t v) { return __builtin_bit_
 
 template <int NT, int MT, bool KTAIL, int NW>
 __global__ __launch_bounds__(64 * NW, 2) void k_gemm_mfma(const bf16* __restrict__ xhi, const bf16* __restrict__ xlo,
-                                                      int ldx, int rows, WSeg w, int n, int K,
+                                                      int ldx, int rows, const char* __restrict__ wpk, int n, int K,
                                                       float* __restrict__ out, int ld_out, size_t part_stride,
                                                       int S, int k_per) {
   constexpr int XROWS = NT * 16;
@@ -50,16 +53,14 @@ __global__ __launch_bounds__(64 * NW, 2) void k_gemm_mfma(const bf16* __restrict
   const int nstages = (k_end - k_begin + KC - 1) / KC;
   const int r16 = lane & 15, kb = lane >> 4;
 
-  // W: lane (r16, kb) reads 16 B at byte j*64 + kb*16 of each 128-byte stage of its row
+  // W: fragment (16-row tile, 32-column step) = 1 KiB, lane's 16 B at byte 16 * lane
+  const int kp32 = ((K + KC - 1) / KC) * 2;   // 32-column steps of a zero-padded row
+  const int n16 = (n + 15) >> 4;
   const char* wp[MT];
 #pragma unroll
   for (int mt = 0; mt < MT; ++mt) {
-    int row = min(n0 + mt * 16 + r16, n - 1);
-    // up to three matrices stacked along n (q|k|v, gate|up) are streamed by one launch
-    const bf16* base = row < w.n0 ? w.w0 + (size_t)row * K
-                       : row < w.n0 + w.n1 ? w.w1 + (size_t)(row - w.n0) * K
-                                           : w.w2 + (size_t)(row - w.n0 - w.n1) * K;
-    wp[mt] = (const char*)base + (size_t)k_begin * 2 + kb * 16;
+    const int t16 = min((n0 >> 4) + mt, n16 - 1);
+    wp[mt] = wpk + ((size_t)t16 * kp32 + (k_begin >> 5)) * 1024 + lane * 16;
   }
   // X: the stage tile is 2 planes x XROWS rows x 8 chunks of 16 B; chunk id -> thread round-robin
   constexpr int XCHUNKS = 2 * XROWS * 8;
@@ -77,18 +78,12 @@ __global__ __launch_bounds__(64 * NW, 2) void k_gemm_mfma(const bf16* __restrict
   }
   const int blds = r16 * PITCH + kb * 16;
 
+  // (the padding of the copy is zero, so the last stage of a ragged K needs no guard here)
   auto load_w = [&](u32x4_t (&a)[MT][2], int stage) {
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-      for (int j = 0; j < 2; ++j) {
-        if constexpr (KTAIL) {
-          bool ok = k_begin + stage * KC + j * 32 + kb * 8 < k_end;
-          a[mt][j] = ok ? *(const u32x4_t*)(wp[mt] + (size_t)stage * (KC * 2) + j * 64) : u32x4_t{0, 0, 0, 0};
-        } else {
-          a[mt][j] = *(const u32x4_t*)(wp[mt] + (size_t)stage * (KC * 2) + j * 64);
-        }
-      }
+      for (int j = 0; j < 2; ++j) a[mt][j] = *(const u32x4_t*)(wp[mt] + (size_t)stage * 2048 + j * 1024);
   };
   auto load_x = [&](u32x4_t (&x)[XP], int stage) {
 #pragma unroll
@@ -180,12 +175,12 @@ __global__ __launch_bounds__(64 * NW, 2) void k_gemm_mfma(const bf16* __restrict
 
 // One translation unit per workgroup size instantiates this for every activation tile count.
 template <int NW>
-void launch_gemm_mfma_nw(const bf16* xhi, const bf16* xlo, int ldx, int rows, WSeg w, int n, int K, float* out,
+void launch_gemm_mfma_nw(const bf16* xhi, const bf16* xlo, int ldx, int rows, const char* w, int n, int K, float* out,
                          int ld, size_t part_stride, const GemmPlan& p, hipStream_t s);
 
 #define FIRP_GEMM_INSTANTIATE(NW)                                                                                      \
   template <int NT>                                                                                                   \
-  static void launch_nt_(const bf16* xhi, const bf16* xlo, int ldx, int rows, WSeg w, int n, int K, float* out, \
+  static void launch_nt_(const bf16* xhi, const bf16* xlo, int ldx, int rows, const char* w, int n, int K, float* out, \
                          int ld, size_t part_stride, const GemmPlan& p, hipStream_t s) {                              \
     dim3 g(p.grid), b(64 * NW);                                                                                       \
     if (K % KC)                                                                                                       \
@@ -196,7 +191,7 @@ void launch_gemm_mfma_nw(const bf16* xhi, const bf16* xlo, int ldx, int rows, WS
                          part_stride, p.S, p.k_per);                                                                  \
   }                                                                                                                   \
   template <>                                                                                                         \
-  void launch_gemm_mfma_nw<NW>(const bf16* xhi, const bf16* xlo, int ldx, int rows, WSeg w, int n, int K,            \
+  void launch_gemm_mfma_nw<NW>(const bf16* xhi, const bf16* xlo, int ldx, int rows, const char* w, int n, int K,     \
                                float* out, int ld, size_t part_stride, const GemmPlan& p, hipStream_t s) {            \
     switch (p.nt) {                                                                                                   \
       case 1: launch_nt_<1>(xhi, xlo, ldx, rows, w, n, K, out, ld, part_stride, p, s); break;                         \

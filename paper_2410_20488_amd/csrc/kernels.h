@@ -108,15 +108,22 @@ struct GemmPlan {
 GemmPlan gemm_mfma_plan_ex(int rows, int n, int K, int S, int nw);
 bool gemm_mfma_supported(int rows, int n, int K);
 GemmPlan gemm_mfma_plan(int rows, int n, int K, int force_split);  // force_split 0 = choose
-// Weight operand: up to three [n_i][K] matrices stacked along n (rows [0,n0) from w0, the next
-// n1 from w1, the rest from w2).  A single matrix has n0 >= n.
+// Up to three row-major [n_i][K] matrices stacked along n (rows [0,n0) from w0, the next n1 from
+// w1, the rest from w2).  A single matrix has n0 >= n.
 struct WSeg {
   const bf16 *w0, *w1, *w2;
   int n0, n1;
 };
 inline WSeg wseg1(const void* w, int n) { return WSeg{(const bf16*)w, nullptr, nullptr, n, 0}; }
+// The kernel streams W from a fragment-major copy: the [n][K] matrix, zero-padded to multiples
+// of 16 rows and 64 columns, cut into 16-row x 32-column fragments; fragment (t, s) is the
+// 1 KiB block number t * (Kpad / 32) + s and holds, at byte 16 * lane, the 8 elements
+// W[16 t + lane % 16][32 s + 8 (lane / 16) ...]: exactly the A operand of one
+// v_mfma_f32_16x16x32_bf16, so that a wave's load instruction covers eight whole cache lines.
+size_t gemm_packed_bytes(int n, int K);
+void launch_pack_weights(const WSeg& src, int n, int K, void* dst, hipStream_t s);
 // partials[s][r][c] at out + s*part_stride + r*ld + c for c < n
-void launch_gemm_mfma(const Act& x, const WSeg& w, float* out, int ld, size_t part_stride, int rows,
+void launch_gemm_mfma(const Act& x, const void* w_packed, float* out, int ld, size_t part_stride, int rows,
                       int n, int K, const GemmPlan& plan, hipStream_t s);
 void launch_split_act(const float* x, int rows, int ld, const Act& out, hipStream_t s);
 void launch_reduce_partials(const Partial& p, float* y, int rows, hipStream_t s);
