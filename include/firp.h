@@ -91,7 +91,10 @@ typedef struct {
   const uint8_t *anchor;  /* NULL = every node is an anchor */
 } firp_tree;
 
-/* Bytes of DEVICE workspace firp_init needs for this description (0 on invalid input). */
+/* Bytes of DEVICE workspace firp_init needs for this description (0 on invalid input).
+ * For a bf16 model this includes a second copy of every projection matrix (q, k, v, o, gate,
+ * up, down, lm-head and the k maps: about the size of the model) in the fragment-major layout
+ * the projection kernel streams; see firp_init. */
 size_t firp_workspace_bytes(const firp_model_desc *desc, int32_t k);
 
 /*
@@ -102,6 +105,11 @@ size_t firp_workspace_bytes(const firp_model_desc *desc, int32_t k);
  *  workspace: DEVICE, >= firp_workspace_bytes, 256-byte aligned, owned by the caller and
  *           used exclusively by this context until firp_destroy.
  *  hip_stream: hipStream_t on which all work is enqueued (0 = the null stream).
+ * firp_init itself touches no device memory.  For a bf16 model the first firp_prefill copies
+ * the projection matrices into the workspace in the kernel's streaming layout (once, on the
+ * stream); from then on the caller's q/k/v/o/gate/up/down/lm-head/proj_w buffers are read
+ * only if the plain kernels are selected with firp_set_option("gemm", 0).  The embedding
+ * table, the norm gains and the biases are always read in place.
  */
 firp_status firp_init(firp_ctx **out, const firp_model_desc *desc, const firp_weights *weights,
                       const void *const *proj_w, const void *const *proj_b, int32_t layer_l,
@@ -182,8 +190,8 @@ firp_status firp_get_gemm_timing(const firp_ctx *ctx, int64_t *launches, double 
 
 /* Standalone entry to the projection kernel for per-kernel parity and bandwidth tests:
  * y[R, n] (DEVICE fp32) = x[R, K] (DEVICE fp32) . w[n, K]^T (DEVICE, `dtype`), on `hip_stream`,
- * using `workspace` (DEVICE, >= firp_gemm_workspace_bytes(R, n, K)) for operand planes and
- * split-K partial sums.  `kind` selects the kernel as the "gemm" option does. */
+ * using `workspace` (DEVICE, >= firp_gemm_workspace_bytes(R, n, K)) for operand planes,
+ * split-K partial sums and (kind 1) the fragment-major copy of w, which every call remakes.  `kind` selects the kernel as the "gemm" option does. */
 size_t firp_gemm_workspace_bytes(int32_t rows, int32_t n, int32_t k_dim);
 firp_status firp_debug_gemm(const float *x, const void *w, float *y, int32_t rows, int32_t n,
                             int32_t k_dim, int32_t dtype, int32_t kind, void *workspace,
