@@ -55,6 +55,7 @@ struct firp_ctx {
   int attn_kind = 0;    // 0 plain, 1 MFMA flash-decode (needs the bf16 planes of q)
   bool cache_clean = false;  // the KV cache holds only finite values (zero-filled once)
   float* attn_scratch = nullptr;
+  void* argmax_scratch = nullptr;
   float2* rope_tab = nullptr;  // [rows][dh/2] (cos, sin) of the running step
   hipStream_t stream = nullptr;
   // weights
@@ -66,6 +67,7 @@ struct firp_ctx {
   // q|k|v and gate|up stacked along n, made on the stream by the first prefill
   std::vector<void*> pk_qkv, pk_o, pk_gu, pk_d, pk_proj;
   void* pk_head = nullptr;
+  bool pk_proj_stacked = false;
   bool packed = false;
   // geometry
   int Rmax = 0, Rpad = 0, slots = 0, qkv_ld = 0, esize = 0;
@@ -111,6 +113,8 @@ struct firp_ctx {
   }
 };
 
+static_assert(FIRP_MAX_K <= 8, "PseudoBias holds 8 maps");
+
 namespace {
 
 bool desc_ok(const firp_model_desc* d, int k, std::string& why) {
@@ -146,6 +150,7 @@ size_t carve(firp_ctx* c, char* base) {
   c->logits = cv.take<float>((size_t)Rp * d.vocab);
   c->attn_scratch = cv.take<float>(attention_mfma_scratch_floats(Rp, d.n_q_heads, d.head_dim));
   c->rope_tab = cv.take<float2>((size_t)Rp * d.head_dim / 2);
+  c->argmax_scratch = cv.take<char>(argmax_scratch_bytes(Rp, d.b_max));
   auto act = [&](Act& a, int ld) {
     a.ld = ld;
     a.f32 = cv.take<float>((size_t)Rp * ld);
@@ -170,7 +175,10 @@ size_t carve(firp_ctx* c, char* base) {
       c->pk_gu[i] = pk(2 * d.d_ffn, d.d_model);
       c->pk_d[i] = pk(d.d_model, d.d_ffn);
     }
+    // the k maps back to back: with d a multiple of 16 this is also the copy of the stacked
+    // [k*d][d] matrix, so one launch can stream all of them
     for (int i = 0; i < c->k; ++i) c->pk_proj[i] = pk(d.d_model, d.d_model);
+    c->pk_proj_stacked = d.d_model % 16 == 0 && (gemm_packed_bytes(d.d_model, d.d_model) % 256) == 0;
     c->pk_head = pk(d.vocab, d.d_model);
   }
   size_t kv_elems = (size_t)d.max_batch * c->kv_seq_stride;
@@ -349,11 +357,19 @@ firp_status forward(firp_ctx* c, int B, int rows_lo, int rows_hi, int n_anchor_r
       if (pending.p) launch_add_partial(c->x, pending, pending_rows, d.d_model, s);
       pending = Partial{};
       launch_gather_rows(c->x, c->pseudo_src, n_anchor_rows, d.d_model, c->act_p, sp, s);
-      for (int i = 0; i < c->k; ++i) {
-        Partial y = project(c, c->act_p, c->pw[i], c->packed ? c->pk_proj[i] : nullptr, n_anchor_rows, d.d_model,
-                            d.d_model, d.d_model, 0, nullptr);
-        launch_scatter_pseudo(y, n_anchor_rows, d.d_model, c->k, i, c->pb.empty() ? nullptr : c->pb[i],
-                              c->dtype, c->x, rows_lo, s);
+      PseudoBias pbias{};
+      for (int i = 0; i < c->k; ++i) pbias.b[i] = c->pb.empty() ? nullptr : c->pb[i];
+      if (c->gemm_kind == 1 && c->packed && c->pk_proj_stacked && gemm_mfma_supported(n_anchor_rows, c->k * d.d_model, d.d_model)) {
+        // the k maps share their input: one projection over the stacked copy, one scatter
+        Partial y = project(c, c->act_p, nullptr, c->pk_proj[0], n_anchor_rows, c->k * d.d_model, d.d_model,
+                            c->k * d.d_model, 0, nullptr);
+        launch_scatter_pseudo(y, n_anchor_rows, d.d_model, c->k, 0, c->k, pbias, c->dtype, c->x, rows_lo, s);
+      } else {
+        for (int i = 0; i < c->k; ++i) {
+          Partial y = project(c, c->act_p, c->pw[i], c->packed ? c->pk_proj[i] : nullptr, n_anchor_rows, d.d_model,
+                              d.d_model, d.d_model, 0, nullptr);
+          launch_scatter_pseudo(y, n_anchor_rows, d.d_model, c->k, i, 1, pbias, c->dtype, c->x, rows_lo, s);
+        }
       }
     }
     if (layer == d.n_layers) {
@@ -364,7 +380,7 @@ firp_status forward(firp_ctx* c, int B, int rows_lo, int rows_hi, int n_anchor_r
       launch_add_rmsnorm(c->x, pending, rows, d.d_model, c->norm_final, c->dtype, d.rms_eps, c->act_d, sp, s);
       Partial lg = project(c, c->act_d, c->lm_head, c->packed ? c->pk_head : nullptr, rows, d.vocab, d.d_model,
                            d.vocab, 0, nullptr);
-      launch_argmax_topb(lg, c->logits, real_rows, rows, d.vocab, d.b_max, c->st.amax, c->st.top, s);
+      launch_argmax_topb(lg, c->logits, real_rows, rows, d.vocab, d.b_max, c->st.amax, c->st.top, c->argmax_scratch, s);
       break;
     }
     // the pending partials cover `pending_rows` rows; rows beyond (new pseudo rows) have none

@@ -64,13 +64,18 @@ void launch_swiglu(const Partial& gate_up, int rows, int d_ffn, const Act& out, 
 // FIRP map (Eq. 3): gather anchor rows of the residual stream as projection input ...
 void launch_gather_rows(const float* x, const int* src_rows, int rows, int d, const Act& out,
                         bool split, hipStream_t s);
-// ... and scatter map i's output (+ bias) to the pseudo rows.
-void launch_scatter_pseudo(const Partial& y, int n_anchor_rows, int d, int k, int i,
-                           const void* bias, int dtype, float* x, int first_pseudo_row,
-                           hipStream_t s);
+// ... and scatter the maps' outputs (+ bias) to the pseudo rows: y holds `k_in_y` maps side by
+// side starting with map i0 (all k of them in one projection, or one map per projection).
+struct PseudoBias {
+  const void* b[8];  // per map, nullptr = none
+};
+void launch_scatter_pseudo(const Partial& y, int n_anchor_rows, int d, int k, int i0, int k_in_y,
+                           const PseudoBias& bias, int dtype, float* x, int first_pseudo_row, hipStream_t s);
 // greedy token of every real row and top-b of every pseudo row; also leaves summed logits.
-void launch_argmax_topb(const Partial& logits, float* logits_out, int real_rows, int rows,
-                        int vocab, int b_max, int* amax, int* top, hipStream_t s);
+// (two launches: per vocabulary segment, then a merge; `scratch` >= argmax_scratch_bytes)
+size_t argmax_scratch_bytes(int rows, int b_max);
+void launch_argmax_topb(const Partial& logits, float* logits_out, int real_rows, int rows, int vocab, int b_max,
+                        int* amax, int* top, void* scratch, hipStream_t s);
 void launch_verify_select(const SeqState& st, const TreeTab& tt, int B, hipStream_t s);
 // move the accepted path's K/V to the front of the step's slots; advances nothing.
 void launch_kv_compact(const KvView& kv_layer0, size_t layer_stride, int n_layers, int B,

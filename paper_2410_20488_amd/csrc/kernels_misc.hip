@@ -246,27 +246,28 @@ void launch_gather_rows(const float* x, const int* src_rows, int rows, int d, co
     hipLaunchKernelGGL(k_gather_rows<false>, dim3(rows), dim3(256), 0, s, x, src_rows, d, out);
 }
 
+// y holds the k maps' outputs side by side (map i in columns [i*d, (i+1)*d)), or one map's output
+// (k_in_y == 1, map index i0).  blockIdx = (anchor row, map, column chunk).
 template <typename BT>
-__global__ void k_scatter_pseudo(Partial y, int d, int k, int i, const BT* __restrict__ bias, float* x,
+__global__ void k_scatter_pseudo(Partial y, int d, int k, int i0, int k_in_y, PseudoBias bias, float* x,
                                  int first_pseudo_row) {
-  int g = blockIdx.x;
+  const int g = blockIdx.x, i = i0 + blockIdx.y;
   float* xr = x + (size_t)(first_pseudo_row + g * k + i) * d;
-  for (int c = threadIdx.x; c < d; c += blockDim.x) {
-    float v = partial_sum(y, (size_t)g * y.ld + c);
-    if (bias) v += to_f32(bias[c]);
-    xr[c] = v;
-  }
+  const BT* bi = (const BT*)bias.b[i];
+  const int c = blockIdx.z * blockDim.x + threadIdx.x;
+  if (c >= d) return;
+  float v = partial_sum(y, (size_t)g * y.ld + (size_t)(k_in_y > 1 ? i : 0) * d + c);
+  if (bi) v += to_f32(bi[c]);
+  xr[c] = v;
 }
 
-void launch_scatter_pseudo(const Partial& y, int n_anchor_rows, int d, int k, int i,
-                           const void* bias, int dtype, float* x, int first_pseudo_row,
-                           hipStream_t s) {
+void launch_scatter_pseudo(const Partial& y, int n_anchor_rows, int d, int k, int i0, int k_in_y,
+                           const PseudoBias& bias, int dtype, float* x, int first_pseudo_row, hipStream_t s) {
+  dim3 g(n_anchor_rows, k_in_y, (d + 255) / 256);
   if (dtype == DT_BF16)
-    hipLaunchKernelGGL(k_scatter_pseudo<bf16>, dim3(n_anchor_rows), dim3(256), 0, s, y, d, k, i,
-                       (const bf16*)bias, x, first_pseudo_row);
+    hipLaunchKernelGGL(k_scatter_pseudo<bf16>, g, dim3(256), 0, s, y, d, k, i0, k_in_y, bias, x, first_pseudo_row);
   else
-    hipLaunchKernelGGL(k_scatter_pseudo<float>, dim3(n_anchor_rows), dim3(256), 0, s, y, d, k, i,
-                       (const float*)bias, x, first_pseudo_row);
+    hipLaunchKernelGGL(k_scatter_pseudo<float>, g, dim3(256), 0, s, y, d, k, i0, k_in_y, bias, x, first_pseudo_row);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -280,22 +281,27 @@ __device__ __forceinline__ bool better(float v, int id, const Best& o) {
   return v > o.v || (v == o.v && id < o.id);
 }
 
-// One pass over the row: every thread keeps the best BM entries of its strided share in
-// registers (sorted insertion), then BM rounds of a block-wide arg-best over the threads'
-// current heads pick the row's top entries in order.
+// Two levels.  k_argmax_part: blockIdx = (row, vocabulary segment); one pass over the segment,
+// every thread keeps the best BM entries of its strided share in registers (sorted insertion),
+// then `want` rounds of a block-wide arg-best over the threads' current heads leave the
+// segment's best entries, in order, in cand[row][segment][BM].  k_argmax_merge: one block per
+// row picks the row's top entries out of the segments' candidates the same way.
+#define FIRP_ARGMAX_SEGS 8
 template <int BM>
-__global__ __launch_bounds__(256) void k_argmax_topb(Partial lg, float* logits_out, int real_rows,
-                                                     int vocab, int b_max, int* amax, int* top) {
+__global__ __launch_bounds__(256) void k_argmax_part(Partial lg, float* logits_out, int real_rows, int vocab,
+                                                     int b_max, Best* __restrict__ cand) {
   __shared__ float sv[256];
   __shared__ int si[256];
-  const int r = blockIdx.x, tid = threadIdx.x;
+  const int r = blockIdx.x, seg = blockIdx.y, tid = threadIdx.x;
   const size_t off = (size_t)r * lg.ld;
   const bool copy = logits_out && (lg.S > 1 || logits_out != lg.p);
   const int want = (r < real_rows) ? 1 : b_max;
+  const int seg_len = ((vocab + FIRP_ARGMAX_SEGS - 1) / FIRP_ARGMAX_SEGS + 3) & ~3;
+  const int t0 = seg * seg_len, t1 = min(vocab, t0 + seg_len);
   Best mine[BM];
 #pragma unroll
   for (int e = 0; e < BM; ++e) mine[e] = Best{-__builtin_inff(), 0x7fffffff};
-  for (int t = tid; t < vocab; t += 256) {
+  for (int t = t0 + tid; t < t1; t += 256) {
     float v = partial_sum(lg, off + t);
     if (copy) logits_out[(size_t)r * vocab + t] = v;
     if (better(v, t, mine[BM - 1])) {
@@ -309,6 +315,7 @@ __global__ __launch_bounds__(256) void k_argmax_topb(Partial lg, float* logits_o
         }
     }
   }
+  Best* out = cand + ((size_t)r * FIRP_ARGMAX_SEGS + seg) * BM;
   for (int p = 0; p < want; ++p) {
     sv[tid] = mine[0].v;
     si[tid] = mine[0].id;
@@ -324,15 +331,47 @@ __global__ __launch_bounds__(256) void k_argmax_topb(Partial lg, float* logits_o
       }
       __syncthreads();
     }
-    int win = si[0];
+    const Best win{sv[0], si[0]};
     __syncthreads();
-    if (win >= vocab) win = 0;  // only when every remaining logit is NaN
-    if (mine[0].id == win) {  // the owner pops its head
+    if (mine[0].id == win.id && win.id != 0x7fffffff) {  // the owner pops its head
 #pragma unroll
       for (int e = 0; e + 1 < BM; ++e) mine[e] = mine[e + 1];
       mine[BM - 1] = Best{-__builtin_inff(), 0x7fffffff};
     }
-    if (tid == 0) {
+    if (tid == 0) out[p] = win;
+  }
+}
+
+template <int BM>
+__global__ __launch_bounds__(64) void k_argmax_merge(const Best* __restrict__ cand, int real_rows, int vocab,
+                                                     int b_max, int* amax, int* top) {
+  const int r = blockIdx.x, lane = threadIdx.x;
+  const int want = (r < real_rows) ? 1 : b_max;
+  // lane = (segment, slot) for up to 8 segments x 8 slots; with BM = 16 a lane holds two slots
+  constexpr int PER = (FIRP_ARGMAX_SEGS * BM + 63) / 64;
+  Best mine[PER];
+#pragma unroll
+  for (int e = 0; e < PER; ++e) {
+    const int idx = lane * PER + e;           // consecutive slots of one segment are in order
+    const int slot = idx % BM;
+    mine[e] = (idx < FIRP_ARGMAX_SEGS * BM && slot < want) ? cand[(size_t)r * FIRP_ARGMAX_SEGS * BM + idx]
+                                                           : Best{-__builtin_inff(), 0x7fffffff};
+  }
+  for (int p = 0; p < want; ++p) {
+    Best m = mine[0];
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+      Best other{__shfl_xor(m.v, o, 64), __shfl_xor(m.id, o, 64)};
+      if (better(other.v, other.id, m)) m = other;
+    }
+    int win = m.id;
+    if (mine[0].id == win && win != 0x7fffffff) {
+#pragma unroll
+      for (int e = 0; e + 1 < PER; ++e) mine[e] = mine[e + 1];
+      mine[PER - 1] = Best{-__builtin_inff(), 0x7fffffff};
+    }
+    if (win >= vocab) win = 0;  // only when every remaining logit is NaN
+    if (lane == 0) {
       if (r < real_rows)
         amax[r] = win;
       else
@@ -341,12 +380,21 @@ __global__ __launch_bounds__(256) void k_argmax_topb(Partial lg, float* logits_o
   }
 }
 
-void launch_argmax_topb(const Partial& logits, float* logits_out, int real_rows, int rows,
-                        int vocab, int b_max, int* amax, int* top, hipStream_t s) {
-  if (b_max <= 8)
-    hipLaunchKernelGGL(k_argmax_topb<8>, dim3(rows), dim3(256), 0, s, logits, logits_out, real_rows, vocab, b_max, amax, top);
-  else
-    hipLaunchKernelGGL(k_argmax_topb<16>, dim3(rows), dim3(256), 0, s, logits, logits_out, real_rows, vocab, b_max, amax, top);
+size_t argmax_scratch_bytes(int rows, int b_max) {
+  return (size_t)rows * FIRP_ARGMAX_SEGS * (b_max <= 8 ? 8 : 16) * sizeof(Best);
+}
+
+void launch_argmax_topb(const Partial& logits, float* logits_out, int real_rows, int rows, int vocab, int b_max,
+                        int* amax, int* top, void* scratch, hipStream_t s) {
+  Best* cand = (Best*)scratch;
+  dim3 g(rows, FIRP_ARGMAX_SEGS);
+  if (b_max <= 8) {
+    hipLaunchKernelGGL(k_argmax_part<8>, g, dim3(256), 0, s, logits, logits_out, real_rows, vocab, b_max, cand);
+    hipLaunchKernelGGL(k_argmax_merge<8>, dim3(rows), dim3(64), 0, s, cand, real_rows, vocab, b_max, amax, top);
+  } else {
+    hipLaunchKernelGGL(k_argmax_part<16>, g, dim3(256), 0, s, logits, logits_out, real_rows, vocab, b_max, cand);
+    hipLaunchKernelGGL(k_argmax_merge<16>, dim3(rows), dim3(64), 0, s, cand, real_rows, vocab, b_max, amax, top);
+  }
 }
 
 // ------------------------------------------------------------------------------------------
