@@ -90,6 +90,24 @@ __device__ __forceinline__ float partial_sum(const Partial& q, size_t idx) {
   return v;
 }
 
+// ---- row scale of an RMSNorm, applied after the projection --------------------------------
+// The norm kernel hands the projection x * gain and leaves the sum of squares of every row in P
+// pieces; the projection is linear, so the consumer of its output multiplies by
+// 1 / sqrt(mean(x^2) + eps) instead.  This lets the norm run on several workgroups per row
+// without a second pass.  ss == nullptr: no scale.
+struct RowScale {
+  const float* ss;   // [rows][FIRP_NORM_PIECES]
+  int pieces;
+  float inv_d, eps;
+};
+#define FIRP_NORM_PIECES 8
+__device__ __forceinline__ float row_scale(const RowScale& rs, int r) {
+  if (!rs.ss) return 1.0f;
+  float t = 0.f;
+  for (int p = 0; p < rs.pieces; ++p) t += rs.ss[(size_t)r * FIRP_NORM_PIECES + p];
+  return 1.0f / sqrtf(t * rs.inv_d + rs.eps);
+}
+
 // ---- per-row tables of one step (device) ---------------------------------------------------
 // Rows of a step: the tree nodes of every sequence first (sequence-major), then the pseudo rows.
 // `local` is the row's index inside its own sequence (node id, or N + pseudo index): its K/V

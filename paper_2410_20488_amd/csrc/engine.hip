@@ -56,6 +56,7 @@ struct firp_ctx {
   bool cache_clean = false;  // the KV cache holds only finite values (zero-filled once)
   float* attn_scratch = nullptr;
   void* argmax_scratch = nullptr;
+  float* norm_ss = nullptr;    // [rows][FIRP_NORM_PIECES] sums of squares left by the last norm
   float2* rope_tab = nullptr;  // [rows][dh/2] (cos, sin) of the running step
   hipStream_t stream = nullptr;
   // weights
@@ -151,6 +152,7 @@ size_t carve(firp_ctx* c, char* base) {
   c->attn_scratch = cv.take<float>(attention_mfma_scratch_floats(Rp, d.n_q_heads, d.head_dim));
   c->rope_tab = cv.take<float2>((size_t)Rp * d.head_dim / 2);
   c->argmax_scratch = cv.take<char>(argmax_scratch_bytes(Rp, d.b_max));
+  c->norm_ss = cv.take<float>((size_t)Rp * FIRP_NORM_PIECES);
   auto act = [&](Act& a, int ld) {
     a.ld = ld;
     a.f32 = cv.take<float>((size_t)Rp * ld);
@@ -348,6 +350,8 @@ firp_status forward(firp_ctx* c, int B, int rows_lo, int rows_hi, int n_anchor_r
   launch_embed(c->embed, c->dtype, c->st.tok, rows_lo, d.d_model, d.vocab, c->x, s);
   launch_rope_table(rt, c->st.p0, rows_hi, d.head_dim, d.rope_base, c->rope_tab, s);
   Partial pending{};  // projection output not yet added to the residual stream
+  // 1/rms of the latest norm, applied by the kernel that consumes the projection behind it
+  const RowScale rs{c->norm_ss, norm_pieces(d.d_model), 1.0f / (float)d.d_model, d.rms_eps};
   int pending_rows = 0;
   for (int layer = 0; layer <= d.n_layers; ++layer) {
     int rows = layer < c->l ? rows_lo : rows_hi;
@@ -377,10 +381,10 @@ firp_status forward(firp_ctx* c, int B, int rows_lo, int rows_hi, int n_anchor_r
         if (pending.p) launch_add_partial(c->x, pending, pending_rows, d.d_model, s);
         break;
       }
-      launch_add_rmsnorm(c->x, pending, rows, d.d_model, c->norm_final, c->dtype, d.rms_eps, c->act_d, sp, s);
+      launch_add_rmsnorm(c->x, pending, rows, d.d_model, c->norm_final, c->dtype, c->act_d, sp, c->norm_ss, s);
       Partial lg = project(c, c->act_d, c->lm_head, c->packed ? c->pk_head : nullptr, rows, d.vocab, d.d_model,
                            d.vocab, 0, nullptr);
-      launch_argmax_topb(lg, c->logits, real_rows, rows, d.vocab, d.b_max, c->st.amax, c->st.top, c->argmax_scratch, s);
+      launch_argmax_topb(lg, rs, c->logits, real_rows, rows, d.vocab, d.b_max, c->st.amax, c->st.top, c->argmax_scratch, s);
       break;
     }
     // the pending partials cover `pending_rows` rows; rows beyond (new pseudo rows) have none
@@ -388,11 +392,11 @@ firp_status forward(firp_ctx* c, int B, int rows_lo, int rows_hi, int n_anchor_r
       launch_add_partial(c->x, pending, pending_rows, d.d_model, s);
       pending = Partial{};
     }
-    launch_add_rmsnorm(c->x, pending, rows, d.d_model, c->n1[layer], c->dtype, d.rms_eps, c->act_d, sp, s);
+    launch_add_rmsnorm(c->x, pending, rows, d.d_model, c->n1[layer], c->dtype, c->act_d, sp, c->norm_ss, s);
     Partial q = project_stacked(c, c->act_d, c->wq[layer], qd, c->wk[layer], kvd, c->wv[layer], kvd,
                                 c->packed ? c->pk_qkv[layer] : nullptr, rows, d.d_model);
     KvView kv = kv_view(c, layer);
-    launch_rope_kv(q, rows, d.n_q_heads, rt, c->st.p0, c->rope_tab, c->act_q, sp, kv, c->dtype, s);
+    launch_rope_kv(q, rs, rows, d.n_q_heads, rt, c->st.p0, c->rope_tab, c->act_q, sp, kv, c->dtype, s);
     if (c->attn_kind == 1 && sp)
       launch_attention_mfma(c->act_q, rows, d.n_q_heads, B, n_local_lo, n_local - n_local_lo, rt, c->st.p0,
                             max_ctx_now, kv, c->attn_scratch, c->act_o, s);
@@ -401,10 +405,10 @@ firp_status forward(firp_ctx* c, int B, int rows_lo, int rows_hi, int n_anchor_r
                               max_ctx_now + n_local, s);
     Partial o = project(c, c->act_o, c->wo[layer], c->packed ? c->pk_o[layer] : nullptr, rows, d.d_model, qd,
                         d.d_model, 0, nullptr);
-    launch_add_rmsnorm(c->x, o, rows, d.d_model, c->n2[layer], c->dtype, d.rms_eps, c->act_d, sp, s);
+    launch_add_rmsnorm(c->x, o, rows, d.d_model, c->n2[layer], c->dtype, c->act_d, sp, c->norm_ss, s);
     Partial g = project_stacked(c, c->act_d, c->wg[layer], d.d_ffn, c->wu[layer], d.d_ffn, nullptr, 0,
                                 c->packed ? c->pk_gu[layer] : nullptr, rows, d.d_model);
-    launch_swiglu(g, rows, d.d_ffn, c->act_f, sp, s);
+    launch_swiglu(g, rs, rows, d.d_ffn, c->act_f, sp, s);
     pending = project(c, c->act_f, c->wd[layer], c->packed ? c->pk_d[layer] : nullptr, rows, d.d_model, d.d_ffn,
                       d.d_model, 0, nullptr);
     pending_rows = rows;

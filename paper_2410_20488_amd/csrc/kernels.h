@@ -48,18 +48,20 @@ void launch_fill_tokens(const SeqState& st, const TreeTab& tt, int B, const int*
                         hipStream_t s);
 void launch_embed(const void* embed, int dtype, const int* tok, int rows, int d, int vocab, float* x,
                   hipStream_t s);
-// x[r] += sum of partials (if part.p), then act = rmsnorm(x[r]) * gain.
-void launch_add_rmsnorm(float* x, const Partial& part, int rows, int d, const void* gain,
-                        int dtype, float eps, const Act& out, bool split, hipStream_t s);
+// x[r] += sum of partials (if part.p), then act = x[r] * gain and ss_out[r][piece] = the row's
+// sums of squares (see RowScale: the 1/rms factor is applied after the projection).
+int norm_pieces(int d);
+void launch_add_rmsnorm(float* x, const Partial& part, int rows, int d, const void* gain, int dtype, const Act& out,
+                        bool split, float* ss_out, hipStream_t s);
 // Only the residual update, no norm output (used before the projection at the FIRP layer).
 void launch_add_partial(float* x, const Partial& part, int rows, int d, hipStream_t s);
 // qkv partials -> rotary q (activation planes, [rows][Hq*dh]) and K / V^T into the cache.
 void launch_rope_table(const RowTab& rt, const int* p0, int rows, int head_dim, float rope_base,
                        float2* tab, hipStream_t s);   // cos/sin of every row's position, once per step
-void launch_rope_kv(const Partial& qkv, int rows, int n_q_heads, const RowTab& rt, const int* p0,
+void launch_rope_kv(const Partial& qkv, const RowScale& rs, int rows, int n_q_heads, const RowTab& rt, const int* p0,
                     const float2* tab, const Act& q_out, bool split, const KvView& kv, int dtype,
                     hipStream_t s);
-void launch_swiglu(const Partial& gate_up, int rows, int d_ffn, const Act& out, bool split,
+void launch_swiglu(const Partial& gate_up, const RowScale& rs, int rows, int d_ffn, const Act& out, bool split,
                    hipStream_t s);
 // FIRP map (Eq. 3): gather anchor rows of the residual stream as projection input ...
 void launch_gather_rows(const float* x, const int* src_rows, int rows, int d, const Act& out,
@@ -74,8 +76,8 @@ void launch_scatter_pseudo(const Partial& y, int n_anchor_rows, int d, int k, in
 // greedy token of every real row and top-b of every pseudo row; also leaves summed logits.
 // (two launches: per vocabulary segment, then a merge; `scratch` >= argmax_scratch_bytes)
 size_t argmax_scratch_bytes(int rows, int b_max);
-void launch_argmax_topb(const Partial& logits, float* logits_out, int real_rows, int rows, int vocab, int b_max,
-                        int* amax, int* top, void* scratch, hipStream_t s);
+void launch_argmax_topb(const Partial& logits, const RowScale& rs, float* logits_out, int real_rows, int rows,
+                        int vocab, int b_max, int* amax, int* top, void* scratch, hipStream_t s);
 void launch_verify_select(const SeqState& st, const TreeTab& tt, int B, hipStream_t s);
 // move the accepted path's K/V to the front of the step's slots; advances nothing.
 void launch_kv_compact(const KvView& kv_layer0, size_t layer_stride, int n_layers, int B,

@@ -51,82 +51,67 @@ void launch_embed(const void* embed, int dtype, const int* tok, int rows, int d,
 }
 
 // ------------------------------------------------------------------------------------------
-// Residual update + RMSNorm: x[r] += sum_s part[s][r]; act[r] = x[r] / sqrt(mean(x^2)+eps) * g.
-// One workgroup (up to 1024 threads) per row; the row stays in registers between the two passes,
-// all loads of a thread are independent 128-bit loads.
+// Residual update + RMSNorm: x[r] += sum_s part[s][r]; act[r] = x[r] * g, and the sum of squares
+// of the row in pieces (the 1/rms factor is applied by whoever consumes the projection of act,
+// see RowScale).  blockIdx = (row, piece): a piece is 1024 columns, one float4 per thread, all
+// loads of a thread independent 128-bit loads.
 template <typename GT, bool SPLIT, bool NORM>
-__global__ __launch_bounds__(1024) void k_add_rmsnorm(float* x, Partial part, int d,
-                                                      const GT* __restrict__ gain, float eps, Act out) {
-  __shared__ float red[16];
-  constexpr int MAXV = 2;  // float4 per thread: d <= 8192 with 1024 threads
-  const int T = blockDim.x;
-  int r = blockIdx.x;
-  float4* xr = (float4*)(x + (size_t)r * d);
-  const int nv = d >> 2;
-  float4 v[MAXV];
+__global__ __launch_bounds__(256) void k_add_rmsnorm(float* x, Partial part, int d, const GT* __restrict__ gain,
+                                                     Act out, float* __restrict__ ss_out) {
+  __shared__ float red[4];
+  const int r = blockIdx.x, piece = blockIdx.y;
+  const int i = piece * 256 + threadIdx.x;   // float4 index in the row
   float ss = 0.f;
+  if (i < (d >> 2)) {
+    float4* xr = (float4*)(x + (size_t)r * d);
+    float4 a = xr[i];
+    if (part.p) {
+      const float* pp = part.p + (size_t)r * part.ld + (size_t)i * 4;
+      float4 q[16];
 #pragma unroll
-  for (int e = 0; e < MAXV; ++e) {
-    int i = threadIdx.x + e * T;
-    if (i < nv) {
-      float4 a = xr[i];
-      if (part.p) {
-        const float* pp = part.p + (size_t)r * part.ld + (size_t)i * 4;
-        float4 q[16];
+      for (int sp = 0; sp < 16; ++sp)
+        if (sp < part.S) q[sp] = *(const float4*)(pp + (size_t)sp * part.stride);
 #pragma unroll
-        for (int sp = 0; sp < 16; ++sp)
-          if (sp < part.S) q[sp] = *(const float4*)(pp + (size_t)sp * part.stride);
-#pragma unroll
-        for (int sp = 0; sp < 16; ++sp)
-          if (sp < part.S) {
-            a.x += q[sp].x;
-            a.y += q[sp].y;
-            a.z += q[sp].z;
-            a.w += q[sp].w;
-          }
-        xr[i] = a;
-      }
-      v[e] = a;
-      ss += a.x * a.x + a.y * a.y + a.z * a.z + a.w * a.w;
+      for (int sp = 0; sp < 16; ++sp)
+        if (sp < part.S) {
+          a.x += q[sp].x;
+          a.y += q[sp].y;
+          a.z += q[sp].z;
+          a.w += q[sp].w;
+        }
+      xr[i] = a;
+    }
+    if constexpr (NORM) {
+      ss = a.x * a.x + a.y * a.y + a.z * a.z + a.w * a.w;
+      act_store4<SPLIT>(out, (size_t)r * out.ld + (size_t)i * 4, a.x * to_f32(gain[i * 4 + 0]),
+                        a.y * to_f32(gain[i * 4 + 1]), a.z * to_f32(gain[i * 4 + 2]), a.w * to_f32(gain[i * 4 + 3]));
     }
   }
   if constexpr (NORM) {
-    ss = block_sum(ss, red);
-    float inv = 1.0f / sqrtf(ss / (float)d + eps);
-#pragma unroll
-    for (int e = 0; e < MAXV; ++e) {
-      int i = threadIdx.x + e * T;
-      if (i < nv) {
-        size_t o = (size_t)r * out.ld + (size_t)i * 4;
-        act_store4<SPLIT>(out, o, v[e].x * inv * to_f32(gain[i * 4 + 0]), v[e].y * inv * to_f32(gain[i * 4 + 1]),
-                          v[e].z * inv * to_f32(gain[i * 4 + 2]), v[e].w * inv * to_f32(gain[i * 4 + 3]));
-      }
-    }
+    ss = block_sum_256(ss, red);
+    if (threadIdx.x == 0) ss_out[(size_t)r * FIRP_NORM_PIECES + piece] = ss;
   }
 }
 
-static int norm_threads(int d) {
-  int t = ((d / 4 + 1) / 2 + 63) / 64 * 64;   // two float4 per thread
-  return std::max(64, std::min(1024, t));
-}
+int norm_pieces(int d) { return (d / 4 + 255) / 256; }
 
-void launch_add_rmsnorm(float* x, const Partial& part, int rows, int d, const void* gain,
-                        int dtype, float eps, const Act& out, bool split, hipStream_t s) {
-  dim3 g(rows), b(norm_threads(d));
+void launch_add_rmsnorm(float* x, const Partial& part, int rows, int d, const void* gain, int dtype, const Act& out,
+                        bool split, float* ss_out, hipStream_t s) {
+  dim3 g(rows, norm_pieces(d)), b(256);
   if (dtype == DT_BF16) {
     if (split)
-      hipLaunchKernelGGL((k_add_rmsnorm<bf16, true, true>), g, b, 0, s, x, part, d, (const bf16*)gain, eps, out);
+      hipLaunchKernelGGL((k_add_rmsnorm<bf16, true, true>), g, b, 0, s, x, part, d, (const bf16*)gain, out, ss_out);
     else
-      hipLaunchKernelGGL((k_add_rmsnorm<bf16, false, true>), g, b, 0, s, x, part, d, (const bf16*)gain, eps, out);
+      hipLaunchKernelGGL((k_add_rmsnorm<bf16, false, true>), g, b, 0, s, x, part, d, (const bf16*)gain, out, ss_out);
   } else {
-    hipLaunchKernelGGL((k_add_rmsnorm<float, false, true>), g, b, 0, s, x, part, d, (const float*)gain, eps, out);
+    hipLaunchKernelGGL((k_add_rmsnorm<float, false, true>), g, b, 0, s, x, part, d, (const float*)gain, out, ss_out);
   }
 }
 
 void launch_add_partial(float* x, const Partial& part, int rows, int d, hipStream_t s) {
   Act none{};
-  hipLaunchKernelGGL((k_add_rmsnorm<float, false, false>), dim3(rows), dim3(norm_threads(d)), 0, s, x, part, d,
-                     (const float*)nullptr, 0.f, none);
+  hipLaunchKernelGGL((k_add_rmsnorm<float, false, false>), dim3(rows, norm_pieces(d)), dim3(256), 0, s, x, part, d,
+                     (const float*)nullptr, none, (float*)nullptr);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -152,15 +137,16 @@ void launch_rope_table(const RowTab& rt, const int* p0, int rows, int head_dim, 
 
 // blockDim = (dh/2, heads per block); blockIdx = (row, head group)
 template <typename KT, bool SPLIT>
-__global__ void k_rope_kv(Partial qkv, int n_q_heads, RowTab rt, const int* __restrict__ p0,
+__global__ void k_rope_kv(Partial qkv, RowScale rs, int n_q_heads, RowTab rt, const int* __restrict__ p0,
                           const float2* __restrict__ tab, Act q_out, KvView kv) {
   int r = blockIdx.x, h = blockIdx.y * blockDim.y + threadIdx.y, j = threadIdx.x;
   int dh = kv.head_dim, half = dh >> 1, Hkv = kv.n_kv_heads;
   if (h >= n_q_heads + 2 * Hkv) return;
   int b = rt.seq[r];
   size_t row_off = (size_t)r * qkv.ld;
-  float x1 = partial_sum(qkv, row_off + (size_t)h * dh + j);
-  float x2 = partial_sum(qkv, row_off + (size_t)h * dh + j + half);
+  const float scale = row_scale(rs, r);
+  float x1 = partial_sum(qkv, row_off + (size_t)h * dh + j) * scale;
+  float x2 = partial_sum(qkv, row_off + (size_t)h * dh + j + half) * scale;
   if (h < n_q_heads + Hkv) {
     float2 cs = tab[(size_t)r * half + j];
     float y1 = x1 * cs.x - x2 * cs.y, y2 = x2 * cs.x + x1 * cs.y;
@@ -183,7 +169,7 @@ __global__ void k_rope_kv(Partial qkv, int n_q_heads, RowTab rt, const int* __re
   }
 }
 
-void launch_rope_kv(const Partial& qkv, int rows, int n_q_heads, const RowTab& rt, const int* p0,
+void launch_rope_kv(const Partial& qkv, const RowScale& rs, int rows, int n_q_heads, const RowTab& rt, const int* p0,
                     const float2* tab, const Act& q_out, bool split, const KvView& kv, int dtype,
                     hipStream_t s) {
   int half = kv.head_dim / 2;
@@ -192,11 +178,11 @@ void launch_rope_kv(const Partial& qkv, int rows, int n_q_heads, const RowTab& r
   dim3 g(rows, (heads + hpb - 1) / hpb), b(half, hpb);
   if (dtype == DT_BF16) {
     if (split)
-      hipLaunchKernelGGL((k_rope_kv<bf16, true>), g, b, 0, s, qkv, n_q_heads, rt, p0, tab, q_out, kv);
+      hipLaunchKernelGGL((k_rope_kv<bf16, true>), g, b, 0, s, qkv, rs, n_q_heads, rt, p0, tab, q_out, kv);
     else
-      hipLaunchKernelGGL((k_rope_kv<bf16, false>), g, b, 0, s, qkv, n_q_heads, rt, p0, tab, q_out, kv);
+      hipLaunchKernelGGL((k_rope_kv<bf16, false>), g, b, 0, s, qkv, rs, n_q_heads, rt, p0, tab, q_out, kv);
   } else {
-    hipLaunchKernelGGL((k_rope_kv<float, false>), g, b, 0, s, qkv, n_q_heads, rt, p0, tab, q_out, kv);
+    hipLaunchKernelGGL((k_rope_kv<float, false>), g, b, 0, s, qkv, rs, n_q_heads, rt, p0, tab, q_out, kv);
   }
 }
 
@@ -204,7 +190,7 @@ void launch_rope_kv(const Partial& qkv, int rows, int n_q_heads, const RowTab& r
 // SwiGLU: act = silu(gate) * up, gate = columns [0,F), up = columns [F,2F) of the partials.
 // Four columns per thread (F % 4 == 0).
 template <bool SPLIT>
-__global__ void k_swiglu(Partial gu, int F, Act out) {
+__global__ void k_swiglu(Partial gu, RowScale rs, int F, Act out) {
   int r = blockIdx.y;
   int j = (blockIdx.x * blockDim.x + threadIdx.x) * 4;
   if (j >= F) return;
@@ -215,17 +201,20 @@ __global__ void k_swiglu(Partial gu, int F, Act out) {
     g.x += a.x; g.y += a.y; g.z += a.z; g.w += a.w;
     u.x += b.x; u.y += b.y; u.z += b.z; u.w += b.w;
   }
+  const float scale = row_scale(rs, r);
+  g.x *= scale; g.y *= scale; g.z *= scale; g.w *= scale;
+  u.x *= scale; u.y *= scale; u.z *= scale; u.w *= scale;
   act_store4<SPLIT>(out, (size_t)r * out.ld + j, g.x / (1.0f + expf(-g.x)) * u.x, g.y / (1.0f + expf(-g.y)) * u.y,
                     g.z / (1.0f + expf(-g.z)) * u.z, g.w / (1.0f + expf(-g.w)) * u.w);
 }
 
-void launch_swiglu(const Partial& gate_up, int rows, int d_ffn, const Act& out, bool split,
+void launch_swiglu(const Partial& gate_up, const RowScale& rs, int rows, int d_ffn, const Act& out, bool split,
                    hipStream_t s) {
   dim3 g((d_ffn / 4 + 255) / 256, rows), b(256);
   if (split)
-    hipLaunchKernelGGL(k_swiglu<true>, g, b, 0, s, gate_up, d_ffn, out);
+    hipLaunchKernelGGL(k_swiglu<true>, g, b, 0, s, gate_up, rs, d_ffn, out);
   else
-    hipLaunchKernelGGL(k_swiglu<false>, g, b, 0, s, gate_up, d_ffn, out);
+    hipLaunchKernelGGL(k_swiglu<false>, g, b, 0, s, gate_up, rs, d_ffn, out);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -288,21 +277,22 @@ __device__ __forceinline__ bool better(float v, int id, const Best& o) {
 // row picks the row's top entries out of the segments' candidates the same way.
 #define FIRP_ARGMAX_SEGS 8
 template <int BM>
-__global__ __launch_bounds__(256) void k_argmax_part(Partial lg, float* logits_out, int real_rows, int vocab,
-                                                     int b_max, Best* __restrict__ cand) {
+__global__ __launch_bounds__(256) void k_argmax_part(Partial lg, RowScale rs, float* logits_out, int real_rows,
+                                                     int vocab, int b_max, Best* __restrict__ cand) {
   __shared__ float sv[256];
   __shared__ int si[256];
   const int r = blockIdx.x, seg = blockIdx.y, tid = threadIdx.x;
   const size_t off = (size_t)r * lg.ld;
-  const bool copy = logits_out && (lg.S > 1 || logits_out != lg.p);
+  const bool copy = logits_out && (lg.S > 1 || logits_out != lg.p || rs.ss);
   const int want = (r < real_rows) ? 1 : b_max;
+  const float scale = row_scale(rs, r);
   const int seg_len = ((vocab + FIRP_ARGMAX_SEGS - 1) / FIRP_ARGMAX_SEGS + 3) & ~3;
   const int t0 = seg * seg_len, t1 = min(vocab, t0 + seg_len);
   Best mine[BM];
 #pragma unroll
   for (int e = 0; e < BM; ++e) mine[e] = Best{-__builtin_inff(), 0x7fffffff};
   for (int t = t0 + tid; t < t1; t += 256) {
-    float v = partial_sum(lg, off + t);
+    float v = partial_sum(lg, off + t) * scale;
     if (copy) logits_out[(size_t)r * vocab + t] = v;
     if (better(v, t, mine[BM - 1])) {
       mine[BM - 1] = Best{v, t};
@@ -384,15 +374,15 @@ size_t argmax_scratch_bytes(int rows, int b_max) {
   return (size_t)rows * FIRP_ARGMAX_SEGS * (b_max <= 8 ? 8 : 16) * sizeof(Best);
 }
 
-void launch_argmax_topb(const Partial& logits, float* logits_out, int real_rows, int rows, int vocab, int b_max,
-                        int* amax, int* top, void* scratch, hipStream_t s) {
+void launch_argmax_topb(const Partial& logits, const RowScale& rs, float* logits_out, int real_rows, int rows,
+                        int vocab, int b_max, int* amax, int* top, void* scratch, hipStream_t s) {
   Best* cand = (Best*)scratch;
   dim3 g(rows, FIRP_ARGMAX_SEGS);
   if (b_max <= 8) {
-    hipLaunchKernelGGL(k_argmax_part<8>, g, dim3(256), 0, s, logits, logits_out, real_rows, vocab, b_max, cand);
+    hipLaunchKernelGGL(k_argmax_part<8>, g, dim3(256), 0, s, logits, rs, logits_out, real_rows, vocab, b_max, cand);
     hipLaunchKernelGGL(k_argmax_merge<8>, dim3(rows), dim3(64), 0, s, cand, real_rows, vocab, b_max, amax, top);
   } else {
-    hipLaunchKernelGGL(k_argmax_part<16>, g, dim3(256), 0, s, logits, logits_out, real_rows, vocab, b_max, cand);
+    hipLaunchKernelGGL(k_argmax_part<16>, g, dim3(256), 0, s, logits, rs, logits_out, real_rows, vocab, b_max, cand);
     hipLaunchKernelGGL(k_argmax_merge<16>, dim3(rows), dim3(64), 0, s, cand, real_rows, vocab, b_max, amax, top);
   }
 }
