@@ -48,9 +48,131 @@ __device__ __forceinline__ int global_row(const SeqRows& sr, int b, int local) {
                                    : sr.real_total + b * sr.n_pseudo_per_seq + (local - sr.n_real_per_seq);
 }
 
+// ------------------------------------------------------------------------------------------
+// Producer of the attention operands for one layer: sums the split-K partials of the q|k|v
+// projection, applies the row scale of the norm before it and the rotary embedding (half-split
+// pairs (j, j + dh/2), cos/sin from the step's table), and writes
+//   Q   as MFMA B-operand fragments: for (sequence, 16-row tile, q head) 2*dh/32 blocks of 1 KiB,
+//       block 2*ds + plane holding at byte 16 * (16 * kb + r16) the 8 dims 32 ds + 8 kb ... of row
+//       16 tile + r16 (plane 0 = hi, 1 = lo), so that the attention kernel loads a fragment with
+//       one fully coalesced instruction;
+//   K   into the cache row of slot p0 + local (16-byte stores);
+//   V^T through an LDS transpose, so that a store instruction writes runs of 16 consecutive
+//       slots of a dim instead of one element of 64 different dims.
+// blockIdx = (sequence * tiles + tile, group of 256/dh heads); dh threads per head: thread
+// (r16, c) owns dims [8c, 8c+8) and their rotation partners [8c + dh/2, ...).
 template <int DH>
-__global__ __launch_bounds__(64 * NWAVES, 1) void k_attention_mfma(const bf16* __restrict__ qhi, const bf16* __restrict__ qlo,
-                                                          int ldq, int n_q_heads, SeqRows sr, int n_local,
+__global__ __launch_bounds__(256) void k_rope_kv_tiles(Partial qkv, RowScale rs, int n_q_heads, SeqRows sr,
+                                                       int n_local, int n_tiles, const int* __restrict__ p0v,
+                                                       const float2* __restrict__ tab, bf16* __restrict__ q_frag,
+                                                       KvView kv) {
+  constexpr int HPB = 256 / DH, HALF = DH / 2, DS = DH / 32;
+  __shared__ unsigned short vt_lds[HPB][16][DH + 8];
+  const int tile = blockIdx.x % n_tiles, b = blockIdx.x / n_tiles;
+  const int hsel = threadIdx.x / DH, t = threadIdx.x % DH;
+  const int Hkv = kv.n_kv_heads, heads = n_q_heads + 2 * Hkv;
+  const int h = blockIdx.y * HPB + hsel;
+  const int r16 = t & 15, c = t >> 4;   // c < DH/16
+  const int local = tile * 16 + r16;
+  const bool valid = local < n_local && h < heads;
+  const int p0 = p0v[b];
+  if (valid) {
+    const int row = global_row(sr, b, local);
+    const float scale = row_scale(rs, row);
+    const size_t col = (size_t)row * qkv.ld + (size_t)h * DH + 8 * c;
+    float x1[8], x2[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) x1[i] = x2[i] = 0.f;
+    for (int sp = 0; sp < qkv.S; ++sp) {
+      const float* pp = qkv.p + (size_t)sp * qkv.stride + col;
+      const float4 a0 = *(const float4*)pp, a1 = *(const float4*)(pp + 4);
+      const float4 b0 = *(const float4*)(pp + HALF), b1 = *(const float4*)(pp + HALF + 4);
+      x1[0] += a0.x; x1[1] += a0.y; x1[2] += a0.z; x1[3] += a0.w;
+      x1[4] += a1.x; x1[5] += a1.y; x1[6] += a1.z; x1[7] += a1.w;
+      x2[0] += b0.x; x2[1] += b0.y; x2[2] += b0.z; x2[3] += b0.w;
+      x2[4] += b1.x; x2[5] += b1.y; x2[6] += b1.z; x2[7] += b1.w;
+    }
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      x1[i] *= scale;
+      x2[i] *= scale;
+    }
+    if (h < n_q_heads + Hkv) {
+      const float2* cs = tab + (size_t)row * HALF + 8 * c;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        const float2 w = cs[i];
+        const float y1 = x1[i] * w.x - x2[i] * w.y, y2 = x2[i] * w.x + x1[i] * w.y;
+        x1[i] = y1;
+        x2[i] = y2;
+      }
+    }
+    if (h < n_q_heads) {
+      bf16* fb = q_frag + ((size_t)(b * n_tiles + tile) * n_q_heads + h) * (size_t)(DS * 2 * 512);
+#pragma unroll
+      for (int half = 0; half < 2; ++half) {
+        const float* x = half ? x2 : x1;
+        const int cc = c + half * (DH / 16);   // chunk of 8 dims: k-step cc/4, k-block cc%4
+        uint4 hi, lo;
+        split2_bf16(x[0], x[1], hi.x, lo.x);
+        split2_bf16(x[2], x[3], hi.y, lo.y);
+        split2_bf16(x[4], x[5], hi.z, lo.z);
+        split2_bf16(x[6], x[7], hi.w, lo.w);
+        bf16* dst = fb + (size_t)((cc >> 2) * 2) * 512 + ((cc & 3) * 16 + r16) * 8;
+        *(uint4*)dst = hi;
+        *(uint4*)(dst + 512) = lo;
+      }
+    } else if (h < n_q_heads + Hkv) {
+      const int hk = h - n_q_heads;
+      bf16* krow = (bf16*)kv.k + (size_t)b * kv.seq_stride + ((size_t)hk * kv.slots + (size_t)(p0 + local)) * DH;
+      uint4 a, bb;
+      a.x = pack2_bf16(x1[0], x1[1]); a.y = pack2_bf16(x1[2], x1[3]);
+      a.z = pack2_bf16(x1[4], x1[5]); a.w = pack2_bf16(x1[6], x1[7]);
+      bb.x = pack2_bf16(x2[0], x2[1]); bb.y = pack2_bf16(x2[2], x2[3]);
+      bb.z = pack2_bf16(x2[4], x2[5]); bb.w = pack2_bf16(x2[6], x2[7]);
+      *(uint4*)(krow + 8 * c) = a;
+      *(uint4*)(krow + 8 * c + HALF) = bb;
+    } else {
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        vt_lds[hsel][r16][8 * c + i] = f32_to_bf16(x1[i]).v;
+        vt_lds[hsel][r16][8 * c + HALF + i] = f32_to_bf16(x2[i]).v;
+      }
+    }
+  }
+  __syncthreads();
+  if (h >= n_q_heads + Hkv && h < heads) {
+    const int hv = h - n_q_heads - Hkv;
+    unsigned short* vt = (unsigned short*)kv.v + (size_t)b * kv.seq_stride + (size_t)hv * DH * kv.slots + p0 + tile * 16;
+    for (int idx = t; idx < DH * 16; idx += DH) {
+      const int dim = idx >> 4, rr = idx & 15;
+      if (tile * 16 + rr < n_local) vt[(size_t)dim * kv.slots + rr] = vt_lds[hsel][rr][dim];
+    }
+  }
+}
+
+size_t attention_q_frag_elems(int rows, int max_batch, int n_q_heads, int head_dim) {
+  return (size_t)(rows + 16 * max_batch) * n_q_heads * head_dim * 2;
+}
+
+void launch_rope_kv_tiles(const Partial& qkv, const RowScale& rs, int n_q_heads, int B, int n_real_per_seq,
+                          int n_pseudo_per_seq, const int* p0, const float2* tab, bf16* q_frag, const KvView& kv,
+                          hipStream_t s) {
+  const int n_local = n_real_per_seq + n_pseudo_per_seq, n_tiles = (n_local + 15) / 16;
+  SeqRows sr{n_real_per_seq, n_pseudo_per_seq, B * n_real_per_seq};
+  const int dh = kv.head_dim, heads = n_q_heads + 2 * kv.n_kv_heads, hpb = 256 / dh;
+  dim3 g(B * n_tiles, (heads + hpb - 1) / hpb), blk(256);
+  if (dh == 128)
+    hipLaunchKernelGGL(k_rope_kv_tiles<128>, g, blk, 0, s, qkv, rs, n_q_heads, sr, n_local, n_tiles, p0, tab, q_frag, kv);
+  else if (dh == 64)
+    hipLaunchKernelGGL(k_rope_kv_tiles<64>, g, blk, 0, s, qkv, rs, n_q_heads, sr, n_local, n_tiles, p0, tab, q_frag, kv);
+  else
+    hipLaunchKernelGGL(k_rope_kv_tiles<32>, g, blk, 0, s, qkv, rs, n_q_heads, sr, n_local, n_tiles, p0, tab, q_frag, kv);
+}
+
+template <int DH>
+__global__ __launch_bounds__(64 * NWAVES, 1) void k_attention_mfma(const bf16* __restrict__ q_frag,
+                                                          int n_q_heads, SeqRows sr, int n_local,
                                                           const unsigned long long* __restrict__ row_mask,
                                                           const int* __restrict__ p0v, KvView kv, int chunk,
                                                           float* __restrict__ part_o, float* __restrict__ part_ml,
@@ -136,11 +258,16 @@ __global__ __launch_bounds__(64 * NWAVES, 1) void k_attention_mfma(const bf16* _
       int row = global_row(sr, b, local);
       row_of[p] = (tile * 16 + r16 < n_local) ? row : -1;
       head_of[p] = hk * G + g;
-      const size_t qoff = (size_t)row * ldq + (size_t)head_of[p] * DH + kb * 8;
+      if (p < n_live) {
+        const bf16* fb = q_frag + ((size_t)(b * n_tiles + tile) * n_q_heads + head_of[p]) * (size_t)(DS * 2 * 512) + lane * 8;
 #pragma unroll
-      for (int ds = 0; ds < DS; ++ds) {
-        q[p][ds][0] = *(const u32x4_t*)(qhi + qoff + ds * 32);
-        q[p][ds][1] = *(const u32x4_t*)(qlo + qoff + ds * 32);
+        for (int ds = 0; ds < DS; ++ds) {
+          q[p][ds][0] = *(const u32x4_t*)(fb + (ds * 2) * 512);
+          q[p][ds][1] = *(const u32x4_t*)(fb + (ds * 2 + 1) * 512);
+        }
+      } else {
+#pragma unroll
+        for (int ds = 0; ds < DS; ++ds) q[p][ds][0] = q[p][ds][1] = u32x4_t{0, 0, 0, 0};
       }
 #pragma unroll
       for (int wd = 0; wd < FIRP_MASK_WORDS; ++wd) mw[p][wd] = row_mask[(size_t)row * FIRP_MASK_WORDS + wd];
@@ -351,7 +478,7 @@ size_t attention_mfma_scratch_floats(int rows, int n_q_heads, int head_dim) {
   return (size_t)rows * n_q_heads * FIRP_ATTN_MAX_SPLITS * (head_dim + 2);
 }
 
-void launch_attention_mfma(const Act& q, int rows, int n_q_heads, int B, int n_real_per_seq, int n_pseudo_per_seq,
+void launch_attention_mfma(const bf16* q_frag, int rows, int n_q_heads, int B, int n_real_per_seq, int n_pseudo_per_seq,
                            const RowTab& rt, const int* p0, int max_ctx_now, const KvView& kv, float* scratch,
                            const Act& out, hipStream_t s) {
   const int n_local = n_real_per_seq + n_pseudo_per_seq;
@@ -368,11 +495,11 @@ void launch_attention_mfma(const Act& q, int rows, int n_q_heads, int B, int n_r
   float* part_ml = scratch + (size_t)rows * n_q_heads * FIRP_ATTN_MAX_SPLITS * dh;
   dim3 g(splits, kv.n_kv_heads, B), blk(64 * NWAVES);
   if (dh == 128)
-    hipLaunchKernelGGL(k_attention_mfma<128>, g, blk, 0, s, q.hi, q.lo, q.ld, n_q_heads, sr, n_local, rt.mask, p0, kv, chunk, part_o, part_ml, splits);
+    hipLaunchKernelGGL(k_attention_mfma<128>, g, blk, 0, s, q_frag, n_q_heads, sr, n_local, rt.mask, p0, kv, chunk, part_o, part_ml, splits);
   else if (dh == 64)
-    hipLaunchKernelGGL(k_attention_mfma<64>, g, blk, 0, s, q.hi, q.lo, q.ld, n_q_heads, sr, n_local, rt.mask, p0, kv, chunk, part_o, part_ml, splits);
+    hipLaunchKernelGGL(k_attention_mfma<64>, g, blk, 0, s, q_frag, n_q_heads, sr, n_local, rt.mask, p0, kv, chunk, part_o, part_ml, splits);
   else
-    hipLaunchKernelGGL(k_attention_mfma<32>, g, blk, 0, s, q.hi, q.lo, q.ld, n_q_heads, sr, n_local, rt.mask, p0, kv, chunk, part_o, part_ml, splits);
+    hipLaunchKernelGGL(k_attention_mfma<32>, g, blk, 0, s, q_frag, n_q_heads, sr, n_local, rt.mask, p0, kv, chunk, part_o, part_ml, splits);
   int hpb = std::max(1, 256 / (dh / 4));
   dim3 gc(rows, (n_q_heads + hpb - 1) / hpb), bc(dh / 4, hpb);
   hipLaunchKernelGGL(k_attn_combine<true>, gc, bc, 0, s, part_o, part_ml, splits, n_q_heads, dh, out);

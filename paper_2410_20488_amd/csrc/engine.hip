@@ -56,6 +56,7 @@ struct firp_ctx {
   bool cache_clean = false;  // the KV cache holds only finite values (zero-filled once)
   float* attn_scratch = nullptr;
   void* argmax_scratch = nullptr;
+  bf16* q_frag = nullptr;      // q of the running layer as MFMA fragments (MFMA attention)
   float* norm_ss = nullptr;    // [rows][FIRP_NORM_PIECES] sums of squares left by the last norm
   float2* rope_tab = nullptr;  // [rows][dh/2] (cos, sin) of the running step
   hipStream_t stream = nullptr;
@@ -153,6 +154,7 @@ size_t carve(firp_ctx* c, char* base) {
   c->rope_tab = cv.take<float2>((size_t)Rp * d.head_dim / 2);
   c->argmax_scratch = cv.take<char>(argmax_scratch_bytes(Rp, d.b_max));
   c->norm_ss = cv.take<float>((size_t)Rp * FIRP_NORM_PIECES);
+  c->q_frag = cv.take<bf16>(attention_q_frag_elems(Rp, d.max_batch, d.n_q_heads, d.head_dim));
   auto act = [&](Act& a, int ld) {
     a.ld = ld;
     a.f32 = cv.take<float>((size_t)Rp * ld);
@@ -396,13 +398,16 @@ firp_status forward(firp_ctx* c, int B, int rows_lo, int rows_hi, int n_anchor_r
     Partial q = project_stacked(c, c->act_d, c->wq[layer], qd, c->wk[layer], kvd, c->wv[layer], kvd,
                                 c->packed ? c->pk_qkv[layer] : nullptr, rows, d.d_model);
     KvView kv = kv_view(c, layer);
-    launch_rope_kv(q, rs, rows, d.n_q_heads, rt, c->st.p0, c->rope_tab, c->act_q, sp, kv, c->dtype, s);
-    if (c->attn_kind == 1 && sp)
-      launch_attention_mfma(c->act_q, rows, d.n_q_heads, B, n_local_lo, n_local - n_local_lo, rt, c->st.p0,
+    if (c->attn_kind == 1 && sp) {
+      launch_rope_kv_tiles(q, rs, d.n_q_heads, B, n_local_lo, n_local - n_local_lo, c->st.p0, c->rope_tab, c->q_frag,
+                           kv, s);
+      launch_attention_mfma(c->q_frag, rows, d.n_q_heads, B, n_local_lo, n_local - n_local_lo, rt, c->st.p0,
                             max_ctx_now, kv, c->attn_scratch, c->act_o, s);
-    else
+    } else {
+      launch_rope_kv(q, rs, rows, d.n_q_heads, rt, c->st.p0, c->rope_tab, c->act_q, sp, kv, c->dtype, s);
       launch_attention_simple(c->act_q, sp, rows, d.n_q_heads, rt, c->st.p0, kv, c->dtype, c->act_o, n_local,
                               max_ctx_now + n_local, s);
+    }
     Partial o = project(c, c->act_o, c->wo[layer], c->packed ? c->pk_o[layer] : nullptr, rows, d.d_model, qd,
                         d.d_model, 0, nullptr);
     launch_add_rmsnorm(c->x, o, rows, d.d_model, c->n2[layer], c->dtype, c->act_d, sp, c->norm_ss, s);

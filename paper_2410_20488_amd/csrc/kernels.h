@@ -95,9 +95,15 @@ void launch_attention_simple(const Act& q, bool split, int rows, int n_q_heads, 
 #define FIRP_ATTN_MAX_SPLITS 16
 bool attention_mfma_supported(int head_dim, int dtype);
 size_t attention_mfma_scratch_floats(int rows, int n_q_heads, int head_dim);
-void launch_attention_mfma(const Act& q, int rows, int n_q_heads, int B, int n_real_per_seq,
+void launch_attention_mfma(const bf16* q_frag, int rows, int n_q_heads, int B, int n_real_per_seq,
                            int n_pseudo_per_seq, const RowTab& rt, const int* p0, int max_ctx_now,
                            const KvView& kv, float* scratch, const Act& out, hipStream_t s);
+// Its operand producer (replaces launch_rope_kv on this path): q as MFMA fragments in q_frag
+// (attention_q_frag_elems bf16 elements), K and V^T into the cache.
+size_t attention_q_frag_elems(int rows, int max_batch, int n_q_heads, int head_dim);
+void launch_rope_kv_tiles(const Partial& qkv, const RowScale& rs, int n_q_heads, int B, int n_real_per_seq,
+                          int n_pseudo_per_seq, const int* p0, const float2* tab, bf16* q_frag, const KvView& kv,
+                          hipStream_t s);
 
 // plain tiled projection: y[S=1][rows][n] = x_f32[rows][K] . W[n][K]^T
 void launch_gemm_simple(const float* x, int ldx, const void* w, int dtype, float* y, int ldy,
