@@ -59,50 +59,56 @@ __device__ __forceinline__ int global_row(const SeqRows& sr, int b, int local) {
 //   K   into the cache row of slot p0 + local (16-byte stores);
 //   V^T through an LDS transpose, so that a store instruction writes runs of 16 consecutive
 //       slots of a dim instead of one element of 64 different dims.
-// blockIdx = (sequence * tiles + tile, group of 256/dh heads); dh threads per head: thread
-// (r16, c) owns dims [8c, 8c+8) and their rotation partners [8c + dh/2, ...).
+// blockIdx = (sequence * tiles + tile, group of 128/dh heads); 2*dh threads per head: thread
+// (r16, c), c fastest, owns dims [4c, 4c+4) and their rotation partners [4c + dh/2, ...), so a
+// wave reads whole rows of the partial sums in 16-byte pieces.
 template <int DH>
 __global__ __launch_bounds__(256) void k_rope_kv_tiles(Partial qkv, RowScale rs, int n_q_heads, SeqRows sr,
                                                        int n_local, int n_tiles, const int* __restrict__ p0v,
                                                        const float2* __restrict__ tab, bf16* __restrict__ q_frag,
                                                        KvView kv) {
-  constexpr int HPB = 256 / DH, HALF = DH / 2, DS = DH / 32;
+  constexpr int TPH = 2 * DH, HPB = 256 / TPH, HALF = DH / 2, DS = DH / 32, CPR = DH / 8;  // chunks per row
   __shared__ unsigned short vt_lds[HPB][16][DH + 8];
   const int tile = blockIdx.x % n_tiles, b = blockIdx.x / n_tiles;
-  const int hsel = threadIdx.x / DH, t = threadIdx.x % DH;
+  const int hsel = threadIdx.x / TPH, t = threadIdx.x % TPH;
   const int Hkv = kv.n_kv_heads, heads = n_q_heads + 2 * Hkv;
   const int h = blockIdx.y * HPB + hsel;
-  const int r16 = t & 15, c = t >> 4;   // c < DH/16
+  const int c = t % CPR, r16 = t / CPR;
   const int local = tile * 16 + r16;
   const bool valid = local < n_local && h < heads;
   const int p0 = p0v[b];
   if (valid) {
     const int row = global_row(sr, b, local);
+    const size_t col = (size_t)row * qkv.ld + (size_t)h * DH + 4 * c;
+    // all splits' loads in flight at once (split-K never exceeds 16)
+    float4 va[16], vb[16];
+#pragma unroll
+    for (int u = 0; u < 16; ++u)
+      if (u < qkv.S) {
+        const float* pp = qkv.p + (size_t)u * qkv.stride + col;
+        va[u] = *(const float4*)pp;
+        vb[u] = *(const float4*)(pp + HALF);
+      }
+    float x1[4] = {0.f, 0.f, 0.f, 0.f}, x2[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int u = 0; u < 16; ++u)
+      if (u < qkv.S) {
+        x1[0] += va[u].x; x1[1] += va[u].y; x1[2] += va[u].z; x1[3] += va[u].w;
+        x2[0] += vb[u].x; x2[1] += vb[u].y; x2[2] += vb[u].z; x2[3] += vb[u].w;
+      }
     const float scale = row_scale(rs, row);
-    const size_t col = (size_t)row * qkv.ld + (size_t)h * DH + 8 * c;
-    float x1[8], x2[8];
 #pragma unroll
-    for (int i = 0; i < 8; ++i) x1[i] = x2[i] = 0.f;
-    for (int sp = 0; sp < qkv.S; ++sp) {
-      const float* pp = qkv.p + (size_t)sp * qkv.stride + col;
-      const float4 a0 = *(const float4*)pp, a1 = *(const float4*)(pp + 4);
-      const float4 b0 = *(const float4*)(pp + HALF), b1 = *(const float4*)(pp + HALF + 4);
-      x1[0] += a0.x; x1[1] += a0.y; x1[2] += a0.z; x1[3] += a0.w;
-      x1[4] += a1.x; x1[5] += a1.y; x1[6] += a1.z; x1[7] += a1.w;
-      x2[0] += b0.x; x2[1] += b0.y; x2[2] += b0.z; x2[3] += b0.w;
-      x2[4] += b1.x; x2[5] += b1.y; x2[6] += b1.z; x2[7] += b1.w;
-    }
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
+    for (int i = 0; i < 4; ++i) {
       x1[i] *= scale;
       x2[i] *= scale;
     }
     if (h < n_q_heads + Hkv) {
-      const float2* cs = tab + (size_t)row * HALF + 8 * c;
+      const float4* cs = (const float4*)(tab + (size_t)row * HALF + 4 * c);
+      const float4 w01 = cs[0], w23 = cs[1];   // (cos, sin) of dims 4c .. 4c+3
+      const float co[4] = {w01.x, w01.z, w23.x, w23.z}, si[4] = {w01.y, w01.w, w23.y, w23.w};
 #pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        const float2 w = cs[i];
-        const float y1 = x1[i] * w.x - x2[i] * w.y, y2 = x2[i] * w.x + x1[i] * w.y;
+      for (int i = 0; i < 4; ++i) {
+        const float y1 = x1[i] * co[i] - x2[i] * si[i], y2 = x2[i] * co[i] + x1[i] * si[i];
         x1[i] = y1;
         x2[i] = y2;
       }
@@ -112,31 +118,24 @@ __global__ __launch_bounds__(256) void k_rope_kv_tiles(Partial qkv, RowScale rs,
 #pragma unroll
       for (int half = 0; half < 2; ++half) {
         const float* x = half ? x2 : x1;
-        const int cc = c + half * (DH / 16);   // chunk of 8 dims: k-step cc/4, k-block cc%4
-        uint4 hi, lo;
+        const int c8 = (c >> 1) + half * (DH / 16);   // chunk of 8 dims: k-step c8/4, k-block c8%4
+        uint2 hi, lo;
         split2_bf16(x[0], x[1], hi.x, lo.x);
         split2_bf16(x[2], x[3], hi.y, lo.y);
-        split2_bf16(x[4], x[5], hi.z, lo.z);
-        split2_bf16(x[6], x[7], hi.w, lo.w);
-        bf16* dst = fb + (size_t)((cc >> 2) * 2) * 512 + ((cc & 3) * 16 + r16) * 8;
-        *(uint4*)dst = hi;
-        *(uint4*)(dst + 512) = lo;
+        bf16* dst = fb + (size_t)((c8 >> 2) * 2) * 512 + ((c8 & 3) * 16 + r16) * 8 + (c & 1) * 4;
+        *(uint2*)dst = hi;
+        *(uint2*)(dst + 512) = lo;
       }
     } else if (h < n_q_heads + Hkv) {
       const int hk = h - n_q_heads;
       bf16* krow = (bf16*)kv.k + (size_t)b * kv.seq_stride + ((size_t)hk * kv.slots + (size_t)(p0 + local)) * DH;
-      uint4 a, bb;
-      a.x = pack2_bf16(x1[0], x1[1]); a.y = pack2_bf16(x1[2], x1[3]);
-      a.z = pack2_bf16(x1[4], x1[5]); a.w = pack2_bf16(x1[6], x1[7]);
-      bb.x = pack2_bf16(x2[0], x2[1]); bb.y = pack2_bf16(x2[2], x2[3]);
-      bb.z = pack2_bf16(x2[4], x2[5]); bb.w = pack2_bf16(x2[6], x2[7]);
-      *(uint4*)(krow + 8 * c) = a;
-      *(uint4*)(krow + 8 * c + HALF) = bb;
+      *(uint2*)(krow + 4 * c) = make_uint2(pack2_bf16(x1[0], x1[1]), pack2_bf16(x1[2], x1[3]));
+      *(uint2*)(krow + 4 * c + HALF) = make_uint2(pack2_bf16(x2[0], x2[1]), pack2_bf16(x2[2], x2[3]));
     } else {
 #pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        vt_lds[hsel][r16][8 * c + i] = f32_to_bf16(x1[i]).v;
-        vt_lds[hsel][r16][8 * c + HALF + i] = f32_to_bf16(x2[i]).v;
+      for (int i = 0; i < 4; ++i) {
+        vt_lds[hsel][r16][4 * c + i] = f32_to_bf16(x1[i]).v;
+        vt_lds[hsel][r16][4 * c + HALF + i] = f32_to_bf16(x2[i]).v;
       }
     }
   }
@@ -144,7 +143,7 @@ __global__ __launch_bounds__(256) void k_rope_kv_tiles(Partial qkv, RowScale rs,
   if (h >= n_q_heads + Hkv && h < heads) {
     const int hv = h - n_q_heads - Hkv;
     unsigned short* vt = (unsigned short*)kv.v + (size_t)b * kv.seq_stride + (size_t)hv * DH * kv.slots + p0 + tile * 16;
-    for (int idx = t; idx < DH * 16; idx += DH) {
+    for (int idx = t; idx < DH * 16; idx += TPH) {
       const int dim = idx >> 4, rr = idx & 15;
       if (tile * 16 + rr < n_local) vt[(size_t)dim * kv.slots + rr] = vt_lds[hsel][rr][dim];
     }
@@ -160,7 +159,7 @@ void launch_rope_kv_tiles(const Partial& qkv, const RowScale& rs, int n_q_heads,
                           hipStream_t s) {
   const int n_local = n_real_per_seq + n_pseudo_per_seq, n_tiles = (n_local + 15) / 16;
   SeqRows sr{n_real_per_seq, n_pseudo_per_seq, B * n_real_per_seq};
-  const int dh = kv.head_dim, heads = n_q_heads + 2 * kv.n_kv_heads, hpb = 256 / dh;
+  const int dh = kv.head_dim, heads = n_q_heads + 2 * kv.n_kv_heads, hpb = 128 / dh;
   dim3 g(B * n_tiles, (heads + hpb - 1) / hpb), blk(256);
   if (dh == 128)
     hipLaunchKernelGGL(k_rope_kv_tiles<128>, g, blk, 0, s, qkv, rs, n_q_heads, sr, n_local, n_tiles, p0, tab, q_frag, kv);
@@ -451,22 +450,35 @@ __global__ void k_attn_combine(const float* __restrict__ part_o, const float* __
   int r = blockIdx.x, h = blockIdx.y * blockDim.y + threadIdx.y;
   if (h >= n_q_heads) return;
   size_t base = ((size_t)r * n_q_heads + h) * splits;
+  // all loads of a thread are issued before any is used (splits <= FIRP_ATTN_MAX_SPLITS = 16)
+  const int d = threadIdx.x * 4;
+  float2 ml[16];
+  float4 v[16];
+#pragma unroll
+  for (int s = 0; s < 16; ++s)
+    if (s < splits) {
+      ml[s] = *(const float2*)(part_ml + (base + s) * 2);
+      v[s] = *(const float4*)(part_o + (base + s) * dh + d);
+    }
   float M = -__builtin_inff();
-  for (int s = 0; s < splits; ++s) M = fmaxf(M, part_ml[(base + s) * 2]);
+#pragma unroll
+  for (int s = 0; s < 16; ++s)
+    if (s < splits) M = fmaxf(M, ml[s].x);
   float L = 0.f;
-  for (int s = 0; s < splits; ++s) L += exp2f(part_ml[(base + s) * 2] - M) * part_ml[(base + s) * 2 + 1];
-  float inv = 1.0f / L;
-  int d = threadIdx.x * 4;
   float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
-  for (int s = 0; s < splits; ++s) {
-    float w = exp2f(part_ml[(base + s) * 2] - M);
-    if (w == 0.f) continue;  // an empty split may hold stale values
-    float4 v = *(const float4*)(part_o + (base + s) * dh + d);
-    acc.x += w * v.x;
-    acc.y += w * v.y;
-    acc.z += w * v.z;
-    acc.w += w * v.w;
-  }
+#pragma unroll
+  for (int s = 0; s < 16; ++s)
+    if (s < splits) {
+      const float w = exp2f(ml[s].x - M);
+      L += w * ml[s].y;
+      if (w != 0.f) {  // an empty split may hold stale values
+        acc.x += w * v[s].x;
+        acc.y += w * v[s].y;
+        acc.z += w * v[s].z;
+        acc.w += w * v[s].w;
+      }
+    }
+  const float inv = 1.0f / L;
   act_store4<SPLIT>(out, (size_t)r * out.ld + (size_t)h * dh + d, acc.x * inv, acc.y * inv, acc.z * inv, acc.w * inv);
 }
 

@@ -195,11 +195,22 @@ __global__ void k_swiglu(Partial gu, RowScale rs, int F, Act out) {
   int j = (blockIdx.x * blockDim.x + threadIdx.x) * 4;
   if (j >= F) return;
   const float* pg = gu.p + (size_t)r * gu.ld + j;
-  float4 g = *(const float4*)pg, u = *(const float4*)(pg + F);
-  for (int sp = 1; sp < gu.S; ++sp) {
-    float4 a = *(const float4*)(pg + (size_t)sp * gu.stride), b = *(const float4*)(pg + F + (size_t)sp * gu.stride);
-    g.x += a.x; g.y += a.y; g.z += a.z; g.w += a.w;
-    u.x += b.x; u.y += b.y; u.z += b.z; u.w += b.w;
+  float4 g = make_float4(0.f, 0.f, 0.f, 0.f), u = g;
+  // four splits' loads in flight at a time
+  for (int sp0 = 0; sp0 < gu.S; sp0 += 4) {
+    float4 a[4], b[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e)
+      if (sp0 + e < gu.S) {
+        a[e] = *(const float4*)(pg + (size_t)(sp0 + e) * gu.stride);
+        b[e] = *(const float4*)(pg + F + (size_t)(sp0 + e) * gu.stride);
+      }
+#pragma unroll
+    for (int e = 0; e < 4; ++e)
+      if (sp0 + e < gu.S) {
+        g.x += a[e].x; g.y += a[e].y; g.z += a[e].z; g.w += a[e].w;
+        u.x += b[e].x; u.y += b[e].y; u.z += b[e].z; u.w += b[e].w;
+      }
   }
   const float scale = row_scale(rs, r);
   g.x *= scale; g.y *= scale; g.z *= scale; g.w *= scale;
