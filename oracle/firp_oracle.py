@@ -9,12 +9,15 @@ What it computes (paper: Methodology / FIRP, Inference stage, Tree attention; Eq
 * a LLaMA-style decoder (the models named in Experiment / Setup): pre-norm RMSNorm, rotary
   position embedding on q and k, softmax attention with grouped KV heads, SwiGLU MLP,
   untied lm-head; every weight is `[out, in]`;
-* the FIRP map of Eq. 3, `h~_i = W_i h + b_i` (i = 1..k), applied to the residual stream that
-  enters decoder layer `firp_layer` for every *anchor* node of the draft tree; the k pseudo
-  hidden states then run through the remaining layers as extra rows with position ids
-  `pos(anchor) + i` (Training stage: "position id j+i"), each seeing the context, the
-  anchor's ancestors, the anchor and the earlier pseudo rows of the same anchor (the
-  ablation's "No masked" setting); real rows never see pseudo rows (losslessness, Eq. 1);
+* the FIRP map of Eq. 3, `h~_i = W_i h + b_i` (i = 1..k), applied for every *anchor* node of the
+  draft tree to the residual stream that enters decoder layer `t_i`, the prediction layer of
+  step i (Training stage: "index of prediction layer for step i"; Setup: three different
+  layers for the three steps; `firp_layer` alone means the same layer for every step); pseudo
+  hidden state i then runs through the layers from `t_i` on as an extra row with position id
+  `pos(anchor) + i` (Training stage: "position id j+i"), seeing the context, the anchor's
+  ancestors, the anchor and the earlier pseudo rows of the same anchor (the ablation's "No
+  masked" setting; with `t_1 <= t_2 <= ...` an earlier pseudo row always exists already); real
+  rows never see pseudo rows (losslessness, Eq. 1);
 * tree attention (Tree attention): the flattened tree keeps each node's original position
   `p0 + depth` and a node attends to the cache, its ancestors and itself only;
 * greedy verification (Inference stage; greedy sampling in Setup): walk from the root,
@@ -112,12 +115,18 @@ def tree_ancestors(parent: Sequence[int], v: int) -> List[int]:
 
 @dataclass
 class StepRows:
-    """Row table of one step: real rows 0..N-1 are the tree nodes, then for every anchor
-    (ascending node id) its k pseudo rows (i ascending)."""
+    """Row table of one step: real rows 0..N-1 are the tree nodes, then the pseudo rows, step by
+    step: for i = 1..k, the i-th pseudo row of every anchor (ascending node id).  With this order
+    the rows that exist at any decoder layer are a prefix of the table."""
     n_nodes: int
     pos_off: List[int]                 # position id minus p0, per row
     sees: List[List[int]]              # step rows visible to each row (including itself)
     pseudo_of: List[tuple]             # per pseudo row: (anchor node, i)
+    anchors: List[int]                 # anchor nodes, ascending
+
+    def pseudo_row(self, v: int, i: int) -> int:
+        """Row of pseudo hidden state i (1-based) of anchor node v."""
+        return self.n_nodes + (i - 1) * len(self.anchors) + self.anchors.index(v)
 
 
 def build_rows(parent: Sequence[int], anchor: Sequence[int], k: int) -> StepRows:
@@ -125,15 +134,14 @@ def build_rows(parent: Sequence[int], anchor: Sequence[int], k: int) -> StepRows
     depth = tree_depths(parent)
     pos_off = list(depth)
     sees = [tree_ancestors(parent, v) + [v] for v in range(n)]
+    anchors = [v for v in range(n) if anchor[v]] if k > 0 else []
     pseudo_of = []
-    for v in range(n):
-        if anchor[v] and k > 0:
-            first = len(pos_off)
-            for i in range(1, k + 1):
-                pos_off.append(depth[v] + i)
-                sees.append(sees[v] + list(range(first, first + i)))
-                pseudo_of.append((v, i))
-    return StepRows(n, pos_off, sees, pseudo_of)
+    for i in range(1, k + 1):
+        for a, v in enumerate(anchors):
+            pos_off.append(depth[v] + i)
+            sees.append(sees[v] + [n + (j - 1) * len(anchors) + a for j in range(1, i + 1)])
+            pseudo_of.append((v, i))
+    return StepRows(n, pos_off, sees, pseudo_of, anchors)
 
 
 # --------------------------------------------------------------------------- the model
@@ -155,11 +163,16 @@ class FirpOracle:
     def __init__(self, *, n_layers: int, d_model: int, n_q_heads: int, n_kv_heads: int,
                  head_dim: int, d_ffn: int, vocab: int, rms_eps: float, rope_base: float,
                  weights: Dict[str, object], firp_layer: int, k: int, b_max: int = 8,
-                 dtype: torch.dtype = torch.float32, kv_round_bf16: bool = False):
+                 dtype: torch.dtype = torch.float32, kv_round_bf16: bool = False,
+                 firp_layers: Optional[Sequence[int]] = None):
         self.L, self.d, self.Hq, self.Hkv, self.dh = n_layers, d_model, n_q_heads, n_kv_heads, head_dim
         self.F, self.V, self.eps, self.base = d_ffn, vocab, rms_eps, rope_base
         self.w, self.l, self.k, self.b_max = weights, firp_layer, k, b_max
         self.dtype, self.kv_round = dtype, kv_round_bf16
+        # prediction layer t_i of every step i = 1..k (non-decreasing); one value for all by default
+        self.layers = [firp_layer] * k if firp_layers is None else [int(t) for t in firp_layers]
+        assert len(self.layers) == k and all(0 <= t <= n_layers for t in self.layers)
+        assert all(a <= b for a, b in zip(self.layers, self.layers[1:])), "prediction layers must not decrease"
         assert 0 <= firp_layer <= n_layers
         if k > 0:
             # The paper's draft size (0.08 B for 13B, 0.05 B for 7B) is k full d x d maps.
@@ -286,32 +299,37 @@ class FirpOracle:
                 vis[r, [p0 + c for c in rows.sees[r]]] = True
             return vis
 
-        # layers below the FIRP layer: real rows only
-        x = self._embed(tok)
-        step_K: List[torch.Tensor] = []
-        step_V: List[torch.Tensor] = []
-        vis_lo = visible_for(N)
-        for layer in range(self.l):
-            x, kk, vv = self._layer(layer, x, pos[:N], self.K[layer], self.V[layer], vis_lo)
-            step_K.append(kk)
-            step_V.append(vv)
+        # Rows present at decoder layer `layer`: the nodes and every pseudo row whose prediction
+        # layer is <= layer.  Eq. 3 is applied to the residual stream entering layer t_i.
+        nA = len(rows.anchors)
 
-        # Eq. 3 on the residual stream entering layer `firp_layer`
-        if rows.pseudo_of:
+        def add_pseudo(x: torch.Tensor, i: int) -> torch.Tensor:
             new_rows = []
-            for (v, i) in rows.pseudo_of:
+            for v in rows.anchors:
                 h = self._W("proj_w", i - 1) @ x[v]
                 if self.w.get("proj_b") is not None:
                     h = h + self._W("proj_b", i - 1)
                 new_rows.append(h)
-            x = torch.cat([x, torch.stack(new_rows)], dim=0)
+            return torch.cat([x, torch.stack(new_rows)], dim=0)
 
-        # remaining layers: all rows
-        vis_hi = visible_for(T_hi)
-        for layer in range(self.l, self.L):
-            x, kk, vv = self._layer(layer, x, pos, self.K[layer], self.V[layer], vis_hi)
+        x = self._embed(tok)
+        step_K: List[torch.Tensor] = []
+        step_V: List[torch.Tensor] = []
+        vis_cache: Dict[int, torch.Tensor] = {}
+        for layer in range(self.L + 1):
+            if nA:
+                for i in range(1, self.k + 1):
+                    if self.layers[i - 1] == layer:
+                        x = add_pseudo(x, i)
+            if layer == self.L:
+                break
+            n_rows = x.shape[0]
+            if n_rows not in vis_cache:
+                vis_cache[n_rows] = visible_for(n_rows)
+            x, kk, vv = self._layer(layer, x, pos[:n_rows], self.K[layer], self.V[layer], vis_cache[n_rows])
             step_K.append(kk)
             step_V.append(vv)
+        assert x.shape[0] == T_hi
 
         logits = self._logits(x)
         amax = [int(torch.argmax(logits[r])) for r in range(N)]
@@ -334,11 +352,10 @@ class FirpOracle:
         # next drafts from the pseudo rows of the node that ends the path
         drafts = None
         if anchor[cur] and self.k > 0:
-            first = N + next(j for j, (v, i) in enumerate(rows.pseudo_of) if v == cur)
             drafts = []
-            for i in range(self.k):
+            for i in range(1, self.k + 1):
                 # stable descending sort: equal logits keep ascending id order
-                order = torch.sort(logits[first + i], descending=True, stable=True).indices.tolist()
+                order = torch.sort(logits[rows.pseudo_row(cur, i)], descending=True, stable=True).indices.tolist()
                 drafts.append([int(t_) for t_ in order[: self.b_max]])
 
         # commit the accepted path

@@ -104,6 +104,11 @@ class ModelConfig:
     rms_eps: float = 1e-5
     rope_base: float = 10000.0
     seed: int = 20488
+    firp_layers: Optional[Tuple[int, ...]] = None   # prediction layer of every step; None = firp_layer for all
+
+    @property
+    def layers(self) -> Tuple[int, ...]:
+        return tuple(self.firp_layers) if self.firp_layers is not None else (self.firp_layer,) * self.k
 
     @property
     def torch_dtype(self) -> torch.dtype:

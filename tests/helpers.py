@@ -25,7 +25,7 @@ def make_oracle(cfg: synth.ModelConfig, weights, dtype=torch.float32, b_max=8, k
                       n_kv_heads=cfg.n_kv_heads, head_dim=cfg.head_dim, d_ffn=cfg.d_ffn,
                       vocab=cfg.vocab, rms_eps=cfg.rms_eps, rope_base=cfg.rope_base,
                       weights=weights, firp_layer=cfg.firp_layer, k=cfg.k, b_max=b_max,
-                      dtype=dtype, kv_round_bf16=kv_round)
+                      dtype=dtype, kv_round_bf16=kv_round, firp_layers=cfg.firp_layers)
 
 
 MICRO = synth.ModelConfig("micro", 3, 64, 4, 2, 16, 96, 128, firp_layer=1, k=2, dtype="f32",

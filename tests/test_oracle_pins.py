@@ -2,6 +2,7 @@
 
 Each test names what it fixes.  Citations are to the paper's sections / equations.
 """
+import dataclasses
 import math
 
 import pytest
@@ -141,13 +142,15 @@ def test_k0_root_only_steps_equal_cache_free_greedy():
     assert got == want
 
 
+@pytest.mark.parametrize("layers", [None, (1, 2), (0, 3), (2, 2)])
 @pytest.mark.parametrize("anchors", ["root", "all"])
-def test_tree_rows_equal_brute_force_per_path(anchors):
+def test_tree_rows_equal_brute_force_per_path(anchors, layers):
     """Tree attention: every node's logits equal a plain causal pass over prompt + its path;
-    every pseudo row equals a plain causal chain with the mapped rows inserted at the FIRP
-    layer (positions +1..+k, each seeing the earlier ones)."""
-    o, w = _micro()
-    cfg = MICRO
+    every pseudo row equals a plain causal chain into which mapped row i is inserted at its
+    prediction layer t_i (positions +1..+k, each seeing the earlier ones).  `layers` None: one
+    layer for all steps; otherwise one per step (Training stage, t_i)."""
+    cfg = MICRO if layers is None else dataclasses.replace(MICRO, firp_layers=layers)
+    o, w = _micro(cfg=cfg)
     prompt = synth.prompt_tokens(21, 7, cfg.vocab).tolist()
     o.prefill(prompt)
     tree = synth.random_tree(5, 9, 3, 3, 0.5) if anchors == "root" else synth.full_tree((2, 2), "all")
@@ -158,6 +161,7 @@ def test_tree_rows_equal_brute_force_per_path(anchors):
     res = o.step(**_tree_args(tree), node_tokens=cand)
     toks = res.node_tokens
     brute = make_oracle(cfg, w, dtype=F64)
+    empty = torch.zeros(0, cfg.n_kv_heads, cfg.head_dim, dtype=F64)
     for v in range(tree.n_nodes):
         path = fo.tree_ancestors(tree.parent, v) + [v]
         seq = committed[:-1] + [toks[u] for u in path]
@@ -166,27 +170,42 @@ def test_tree_rows_equal_brute_force_per_path(anchors):
         if tree.anchor[v]:
             n = len(seq)
             x = brute._embed(seq)
-            empty = torch.zeros(0, cfg.n_kv_heads, cfg.head_dim, dtype=F64)
-            for layer in range(cfg.firp_layer):
-                x, _, _ = brute._layer(layer, x, torch.arange(n), empty, empty,
-                                       torch.tril(torch.ones(n, n, dtype=torch.bool)))
-            extra = [w["proj_w"][i].double() @ x[-1] + w["proj_b"][i].double() for i in range(cfg.k)]
-            x = torch.cat([x, torch.stack(extra)])
-            m = n + cfg.k
-            for layer in range(cfg.firp_layer, cfg.n_layers):
+            for layer in range(cfg.n_layers + 1):
+                for i in range(cfg.k):          # step i+1 enters at its own layer, after the earlier steps
+                    if cfg.layers[i] == layer:
+                        assert x.shape[0] == n + i
+                        x = torch.cat([x, (w["proj_w"][i].double() @ x[n - 1] + w["proj_b"][i].double())[None]])
+                if layer == cfg.n_layers:
+                    break
+                m = x.shape[0]
                 x, _, _ = brute._layer(layer, x, torch.arange(m), empty, empty,
                                        torch.tril(torch.ones(m, m, dtype=torch.bool)))
             ref_p = brute._logits(x)[n:]
-            first = tree.n_nodes + [a for a, _ in res.rows.pseudo_of].index(v)
-            assert (res.logits[first:first + cfg.k] - ref_p).abs().max() < 1e-9, f"pseudo of {v}"
+            for i in range(cfg.k):
+                got = res.logits[res.rows.pseudo_row(v, i + 1)]
+                assert (got - ref_p[i]).abs().max() < 1e-9, f"pseudo {i + 1} of {v}"
 
 
-@pytest.mark.parametrize("anchors,seed", [("root", 1), ("all", 2), ("none", 3)])
-def test_losslessness_against_cache_free_greedy(anchors, seed):
-    """Whatever the tree, anchors and (untrained) maps, the concatenated step outputs are the
-    sequential greedy continuation (Eq. 1, 'lossless')."""
-    o, _ = _micro()
-    cfg = MICRO
+def test_one_prediction_layer_for_all_steps_is_the_special_case():
+    """Per-step layers that happen to be equal give exactly the single-layer result."""
+    prompt = synth.prompt_tokens(23, 6, MICRO.vocab).tolist()
+    tree = synth.full_tree((2, 2), "all")
+    cand = _random_candidates(5, tree.n_nodes, MICRO.vocab)
+    outs = []
+    for cfg in (MICRO, dataclasses.replace(MICRO, firp_layers=(MICRO.firp_layer,) * MICRO.k)):
+        o, _ = _micro(cfg=cfg)
+        o.prefill(prompt)
+        outs.append(o.step(**_tree_args(tree), node_tokens=cand).logits)
+    assert torch.equal(outs[0], outs[1])
+
+
+@pytest.mark.parametrize("anchors,seed,layers", [("root", 1, None), ("all", 2, None), ("none", 3, None),
+                                                 ("all", 4, (0, 2)), ("root", 5, (1, 3))])
+def test_losslessness_against_cache_free_greedy(anchors, seed, layers):
+    """Whatever the tree, anchors, prediction layers and (untrained) maps, the concatenated step
+    outputs are the sequential greedy continuation (Eq. 1, 'lossless')."""
+    cfg = MICRO if layers is None else dataclasses.replace(MICRO, firp_layers=layers)
+    o, _ = _micro(cfg=cfg)
     prompt = synth.prompt_tokens(30 + seed, 6, cfg.vocab).tolist()
     m = 14
     want = o.greedy(prompt, m)
@@ -279,7 +298,9 @@ def test_real_rows_do_not_depend_on_pseudo_rows_or_non_ancestors():
     o2.prefill(prompt)
     alt = o2.step(**_tree_args(synth.with_anchors(tree, "root")), node_tokens=cand).logits
     assert torch.equal(base[:tree.n_nodes], alt[:tree.n_nodes])
-    assert not torch.equal(base[tree.n_nodes:tree.n_nodes + cfg.k], alt[tree.n_nodes:])
+    n_anchor_all = tree.n_nodes
+    root_rows = [tree.n_nodes + i * n_anchor_all for i in range(cfg.k)]   # root's pseudo rows among all anchors'
+    assert not torch.equal(base[root_rows], alt[tree.n_nodes:])
     # a node outside the ancestor set of node 3 (= child of node 1): change node 2's token
     cand2 = list(cand)
     cand2[2] = (cand2[2] + 1) % cfg.vocab
@@ -291,11 +312,12 @@ def test_real_rows_do_not_depend_on_pseudo_rows_or_non_ancestors():
 
 def test_position_ids_of_tree_and_pseudo_rows():
     rows = fo.build_rows([-1, 0, 0, 1, 3], [1, 0, 0, 1, 0], 2)
-    assert rows.pos_off == [0, 1, 1, 2, 3, 1, 2, 3, 4]       # siblings share a position id
-    assert rows.pseudo_of == [(0, 1), (0, 2), (3, 1), (3, 2)]
+    assert rows.pos_off == [0, 1, 1, 2, 3, 1, 3, 2, 4]       # siblings share a position id
+    assert rows.pseudo_of == [(0, 1), (3, 1), (0, 2), (3, 2)]   # step by step, anchors ascending
     assert rows.sees[4] == [0, 1, 3, 4]
-    assert rows.sees[6] == [0, 5, 6]                         # second pseudo row sees the first
-    assert rows.sees[7] == [0, 1, 3, 7] and rows.sees[8] == [0, 1, 3, 7, 8]
+    assert rows.sees[7] == [0, 5, 7]                         # second pseudo row sees the first
+    assert rows.sees[6] == [0, 1, 3, 6] and rows.sees[8] == [0, 1, 3, 6, 8]
+    assert rows.pseudo_row(3, 2) == 8 and rows.pseudo_row(0, 1) == 5
 
 
 def test_ties_go_to_the_lower_token_id():
