@@ -116,6 +116,20 @@ firp_status firp_init(firp_ctx **out, const firp_model_desc *desc, const firp_we
                       int32_t k, void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /*
+ * The same with one prediction layer per step (Training stage: "the index of prediction layer
+ * for step i", t_i; Experiment / Setup uses three different layers for the three steps):
+ *  layers: HOST array of k entries, 0 <= layers[0] <= ... <= layers[k-1] <= n_layers; pseudo
+ *          hidden state i+1 of an anchor is W_i h + b_i of the anchor's residual stream entering
+ *          decoder layer layers[i] and traverses the layers from there on, so the step carries
+ *          N rows below layers[0] and N + (i+1) * anchors rows from layers[i] on.
+ * firp_init(layer_l) is firp_init_layers with every entry equal to layer_l.
+ */
+firp_status firp_init_layers(firp_ctx **out, const firp_model_desc *desc, const firp_weights *weights,
+                             const void *const *proj_w, const void *const *proj_b,
+                             const int32_t *layers, int32_t k, void *workspace,
+                             size_t workspace_bytes, void *hip_stream);
+
+/*
  * Start `batch` sequences (Inference stage, first round): run the prompt through the decoder
  * to fill the cache, then a root-only step on the last prompt token.
  *  tokens: HOST, the prompts concatenated; lens: HOST [batch], each >= 1 and <= max_ctx.

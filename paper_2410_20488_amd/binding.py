@@ -63,6 +63,8 @@ def load_library() -> C.CDLL:
         "firp_workspace_bytes": (C.c_size_t, [C.POINTER(ModelDesc), C.c_int32]),
         "firp_init": (C.c_int, [C.POINTER(vp), C.POINTER(ModelDesc), C.POINTER(Weights), C.POINTER(vp),
                                  C.POINTER(vp), C.c_int32, C.c_int32, vp, C.c_size_t, vp]),
+        "firp_init_layers": (C.c_int, [C.POINTER(vp), C.POINTER(ModelDesc), C.POINTER(Weights), C.POINTER(vp),
+                                        C.POINTER(vp), i32p, C.c_int32, vp, C.c_size_t, vp]),
         "firp_prefill": (C.c_int, [vp, C.c_int32, i32p, i32p, i32p]),
         "firp_step": (C.c_int, [vp, C.POINTER(Tree), i32p, i32p]),
         "firp_reset": (C.c_int, [vp]),
@@ -88,7 +90,7 @@ def load_library() -> C.CDLL:
     return lib
 
 
-EXPORTED = ["firp_workspace_bytes", "firp_init", "firp_prefill", "firp_step", "firp_reset", "firp_destroy",
+EXPORTED = ["firp_workspace_bytes", "firp_init", "firp_init_layers", "firp_prefill", "firp_step", "firp_reset", "firp_destroy",
             "firp_last_error", "firp_step_with_candidates", "firp_check_tree", "firp_debug_last_logits", "firp_debug_last_path",
             "firp_get_drafts", "firp_get_ctx_len", "firp_debug_read_cache", "firp_set_option", "firp_get_gemm_timing",
             "firp_gemm_workspace_bytes", "firp_debug_gemm"]
@@ -122,7 +124,7 @@ class Engine:
                  d_ffn: int, vocab: int, rms_eps: float, rope_base: float, dtype: str,
                  weights: Dict[str, object], firp_layer: int, k: int, max_ctx: int, max_batch: int = 1,
                  max_nodes: int = 64, max_rows: int = 128, b_max: int = 8,
-                 stream: Optional[torch.cuda.Stream] = None):
+                 stream: Optional[torch.cuda.Stream] = None, firp_layers: Optional[Sequence[int]] = None):
         self.lib = load_library()
         dev = weights["embed"].device
         if dev.type != "cuda":
@@ -163,10 +165,16 @@ class Engine:
         base = (self.workspace.data_ptr() + 255) // 256 * 256
         self.stream = stream if stream is not None else torch.cuda.current_stream(dev)
         ctx = C.c_void_p()
-        rc = self.lib.firp_init(C.byref(ctx), C.byref(self.desc), C.byref(w),
-                                None if pw is None else C.cast(pw, C.POINTER(C.c_void_p)),
-                                None if pb is None else C.cast(pb, C.POINTER(C.c_void_p)),
-                                firp_layer, k, base, nbytes, self.stream.cuda_stream)
+        pwp = None if pw is None else C.cast(pw, C.POINTER(C.c_void_p))
+        pbp = None if pb is None else C.cast(pb, C.POINTER(C.c_void_p))
+        if firp_layers is None:
+            rc = self.lib.firp_init(C.byref(ctx), C.byref(self.desc), C.byref(w), pwp, pbp, firp_layer, k, base,
+                                    nbytes, self.stream.cuda_stream)
+        else:      # one prediction layer per step
+            assert len(firp_layers) == k
+            layers = _i32(list(firp_layers))
+            rc = self.lib.firp_init_layers(C.byref(ctx), C.byref(self.desc), C.byref(w), pwp, pbp, _p(layers), k,
+                                           base, nbytes, self.stream.cuda_stream)
         if rc != 0:
             raise FirpError(rc, self.lib.firp_last_error(None).decode())
         self.ctx = ctx

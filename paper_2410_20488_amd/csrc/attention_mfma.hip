@@ -37,15 +37,20 @@ constexpr int PAIRS = 2;
 constexpr int NWAVES = 8;
 }  // namespace
 
-// Where the rows of one sequence live in the step's global row order: local id -> row.
+// Where the rows of one sequence live in the step's global row order: local id -> row.  The
+// tree nodes of all sequences come first (sequence-major); the pseudo rows follow step by step:
+// pseudo row i of anchor a of sequence b has local id N + i*A + a and sits behind the pseudo rows
+// of all earlier steps of all sequences, so that the rows alive at a layer are a prefix.
 struct SeqRows {
-  int n_real_per_seq;    // N
-  int n_pseudo_per_seq;  // P (0 in the layers below the FIRP layer)
-  int real_total;        // B * N
+  int n_real_per_seq;     // N
+  int n_anchor_per_seq;   // A
+  int real_total;         // B * N
+  int anchor_total;       // B * A
 };
 __device__ __forceinline__ int global_row(const SeqRows& sr, int b, int local) {
-  return local < sr.n_real_per_seq ? b * sr.n_real_per_seq + local
-                                   : sr.real_total + b * sr.n_pseudo_per_seq + (local - sr.n_real_per_seq);
+  if (local < sr.n_real_per_seq) return b * sr.n_real_per_seq + local;
+  const int q = local - sr.n_real_per_seq, i = q / sr.n_anchor_per_seq, a = q - i * sr.n_anchor_per_seq;
+  return sr.real_total + i * sr.anchor_total + b * sr.n_anchor_per_seq + a;
 }
 
 // ------------------------------------------------------------------------------------------
@@ -155,10 +160,10 @@ size_t attention_q_frag_elems(int rows, int max_batch, int n_q_heads, int head_d
 }
 
 void launch_rope_kv_tiles(const Partial& qkv, const RowScale& rs, int n_q_heads, int B, int n_real_per_seq,
-                          int n_pseudo_per_seq, const int* p0, const float2* tab, bf16* q_frag, const KvView& kv,
-                          hipStream_t s) {
+                          int n_pseudo_per_seq, int n_anchor_per_seq, const int* p0, const float2* tab, bf16* q_frag,
+                          const KvView& kv, hipStream_t s) {
   const int n_local = n_real_per_seq + n_pseudo_per_seq, n_tiles = (n_local + 15) / 16;
-  SeqRows sr{n_real_per_seq, n_pseudo_per_seq, B * n_real_per_seq};
+  SeqRows sr{n_real_per_seq, std::max(1, n_anchor_per_seq), B * n_real_per_seq, B * n_anchor_per_seq};
   const int dh = kv.head_dim, heads = n_q_heads + 2 * kv.n_kv_heads, hpb = 128 / dh;
   dim3 g(B * n_tiles, (heads + hpb - 1) / hpb), blk(256);
   if (dh == 128)
@@ -491,11 +496,11 @@ size_t attention_mfma_scratch_floats(int rows, int n_q_heads, int head_dim) {
 }
 
 void launch_attention_mfma(const bf16* q_frag, int rows, int n_q_heads, int B, int n_real_per_seq, int n_pseudo_per_seq,
-                           const RowTab& rt, const int* p0, int max_ctx_now, const KvView& kv, float* scratch,
+                           int n_anchor_per_seq, const RowTab& rt, const int* p0, int max_ctx_now, const KvView& kv, float* scratch,
                            const Act& out, hipStream_t s) {
   const int n_local = n_real_per_seq + n_pseudo_per_seq;
   const int dh = kv.head_dim;
-  SeqRows sr{n_real_per_seq, n_pseudo_per_seq, B * n_real_per_seq};
+  SeqRows sr{n_real_per_seq, std::max(1, n_anchor_per_seq), B * n_real_per_seq, B * n_anchor_per_seq};
   // chunks of whole 32-key blocks; about one workgroup per CU
   int n_keys = max_ctx_now + n_local;
   int blocks = (n_keys + 31) / 32;

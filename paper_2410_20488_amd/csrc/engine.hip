@@ -49,7 +49,8 @@ struct HostTree {
 
 struct firp_ctx {
   firp_model_desc d{};
-  int k = 0, l = 0, dtype = 0;
+  int k = 0, dtype = 0;
+  std::vector<int> tl;  // prediction layer of every step (k entries, non-decreasing)
   bool split = false;   // activations as hi/lo bf16 planes (MFMA projection)
   int gemm_kind = 0;    // 0 plain, 1 MFMA
   int attn_kind = 0;    // 0 plain, 1 MFMA flash-decode (needs the bf16 planes of q)
@@ -251,7 +252,8 @@ KvView kv_view(const firp_ctx* c, int layer) {
 
 RowTab row_tab(const firp_ctx* c) { return RowTab{c->rt_seq, c->rt_local, c->rt_pos, c->rt_mask}; }
 TreeTab tree_tab(const firp_ctx* c, int N, int P) {
-  return TreeTab{c->tt_parent, c->tt_level, c->tt_rank, c->tt_cstart, c->tt_clist, c->tt_pbase, N, P};
+  return TreeTab{c->tt_parent, c->tt_level, c->tt_rank, c->tt_cstart, c->tt_clist, c->tt_pbase, N, P,
+                 c->k > 0 ? P / c->k : 0};
 }
 
 // y = act . W^T into the partial-sum buffer at column `col` of rows that are `ld` wide.
@@ -339,45 +341,52 @@ void ensure_packed(firp_ctx* c) {
   c->packed = true;
 }
 
-// The decoder over `rows_lo` rows for layers < l and `rows_hi` rows from layer l on.  With
+// The decoder over B sequences of N real rows each; with n_anchor > 0 the pseudo rows of step i
+// (n_anchor per sequence) join at layer tl[i] (Eq. 3 on the residual stream entering it).  With
 // `head`, ends with final norm, lm-head and argmax / top-b.
-firp_status forward(firp_ctx* c, int B, int rows_lo, int rows_hi, int n_anchor_rows, int n_local_lo,
-                    int n_local_hi, int real_rows, bool head, int max_ctx_now) {
+firp_status forward(firp_ctx* c, int B, int N, int n_anchor, bool head, int max_ctx_now) {
   if (c->gemm_kind == 1) ensure_packed(c);
   const firp_model_desc& d = c->d;
   hipStream_t s = c->stream;
   RowTab rt = row_tab(c);
   const bool sp = c->split;
   const int qd = d.n_q_heads * d.head_dim, kvd = d.n_kv_heads * d.head_dim;
-  launch_embed(c->embed, c->dtype, c->st.tok, rows_lo, d.d_model, d.vocab, c->x, s);
-  launch_rope_table(rt, c->st.p0, rows_hi, d.head_dim, d.rope_base, c->rope_tab, s);
+  const int real_rows = B * N, n_anchor_rows = B * n_anchor;
+  const int k_act = n_anchor > 0 ? c->k : 0;
+  launch_embed(c->embed, c->dtype, c->st.tok, real_rows, d.d_model, d.vocab, c->x, s);
+  launch_rope_table(rt, c->st.p0, real_rows + k_act * n_anchor_rows, d.head_dim, d.rope_base, c->rope_tab, s);
   Partial pending{};  // projection output not yet added to the residual stream
   // 1/rms of the latest norm, applied by the kernel that consumes the projection behind it
   const RowScale rs{c->norm_ss, norm_pieces(d.d_model), 1.0f / (float)d.d_model, d.rms_eps};
   int pending_rows = 0;
+  int m = 0;  // steps whose pseudo rows are alive
+  PseudoBias pbias{};
+  for (int i = 0; i < c->k; ++i) pbias.b[i] = c->pb.empty() ? nullptr : c->pb[i];
   for (int layer = 0; layer <= d.n_layers; ++layer) {
-    int rows = layer < c->l ? rows_lo : rows_hi;
-    int n_local = layer < c->l ? n_local_lo : n_local_hi;
-    if (layer == c->l && rows_hi > rows_lo) {
-      // FIRP map (Eq. 3) on the raw residual stream of the anchor rows
+    int m_new = m;
+    while (m_new < k_act && c->tl[m_new] == layer) ++m_new;
+    if (m_new > m) {
+      // FIRP map (Eq. 3) of steps [m, m_new) on the raw residual stream of the anchor rows
       if (pending.p) launch_add_partial(c->x, pending, pending_rows, d.d_model, s);
       pending = Partial{};
       launch_gather_rows(c->x, c->pseudo_src, n_anchor_rows, d.d_model, c->act_p, sp, s);
-      PseudoBias pbias{};
-      for (int i = 0; i < c->k; ++i) pbias.b[i] = c->pb.empty() ? nullptr : c->pb[i];
-      if (c->gemm_kind == 1 && c->packed && c->pk_proj_stacked && gemm_mfma_supported(n_anchor_rows, c->k * d.d_model, d.d_model)) {
-        // the k maps share their input: one projection over the stacked copy, one scatter
-        Partial y = project(c, c->act_p, nullptr, c->pk_proj[0], n_anchor_rows, c->k * d.d_model, d.d_model,
-                            c->k * d.d_model, 0, nullptr);
-        launch_scatter_pseudo(y, n_anchor_rows, d.d_model, c->k, 0, c->k, pbias, c->dtype, c->x, rows_lo, s);
+      const int nm = m_new - m;
+      if (c->gemm_kind == 1 && c->packed && c->pk_proj_stacked && gemm_mfma_supported(n_anchor_rows, nm * d.d_model, d.d_model)) {
+        // the maps share their input: one projection over the stacked copy, one scatter
+        Partial y = project(c, c->act_p, nullptr, c->pk_proj[m], n_anchor_rows, nm * d.d_model, d.d_model,
+                            nm * d.d_model, 0, nullptr);
+        launch_scatter_pseudo(y, n_anchor_rows, d.d_model, c->k, m, nm, pbias, c->dtype, c->x, real_rows, s);
       } else {
-        for (int i = 0; i < c->k; ++i) {
+        for (int i = m; i < m_new; ++i) {
           Partial y = project(c, c->act_p, c->pw[i], c->packed ? c->pk_proj[i] : nullptr, n_anchor_rows, d.d_model,
                               d.d_model, d.d_model, 0, nullptr);
-          launch_scatter_pseudo(y, n_anchor_rows, d.d_model, c->k, i, 1, pbias, c->dtype, c->x, rows_lo, s);
+          launch_scatter_pseudo(y, n_anchor_rows, d.d_model, c->k, i, 1, pbias, c->dtype, c->x, real_rows, s);
         }
       }
+      m = m_new;
     }
+    const int rows = real_rows + m * n_anchor_rows;
+    const int n_local = N + m * n_anchor;
     if (layer == d.n_layers) {
       if (!head) {
         if (pending.p) launch_add_partial(c->x, pending, pending_rows, d.d_model, s);
@@ -399,10 +408,9 @@ firp_status forward(firp_ctx* c, int B, int rows_lo, int rows_hi, int n_anchor_r
                                 c->packed ? c->pk_qkv[layer] : nullptr, rows, d.d_model);
     KvView kv = kv_view(c, layer);
     if (c->attn_kind == 1 && sp) {
-      launch_rope_kv_tiles(q, rs, d.n_q_heads, B, n_local_lo, n_local - n_local_lo, c->st.p0, c->rope_tab, c->q_frag,
-                           kv, s);
-      launch_attention_mfma(c->q_frag, rows, d.n_q_heads, B, n_local_lo, n_local - n_local_lo, rt, c->st.p0,
-                            max_ctx_now, kv, c->attn_scratch, c->act_o, s);
+      launch_rope_kv_tiles(q, rs, d.n_q_heads, B, N, n_local - N, n_anchor, c->st.p0, c->rope_tab, c->q_frag, kv, s);
+      launch_attention_mfma(c->q_frag, rows, d.n_q_heads, B, N, n_local - N, n_anchor, rt, c->st.p0, max_ctx_now, kv,
+                            c->attn_scratch, c->act_o, s);
     } else {
       launch_rope_kv(q, rs, rows, d.n_q_heads, rt, c->st.p0, c->rope_tab, c->act_q, sp, kv, c->dtype, s);
       launch_attention_simple(c->act_q, sp, rows, d.n_q_heads, rt, c->st.p0, kv, c->dtype, c->act_o, n_local,
@@ -439,7 +447,7 @@ firp_status upload_tree(firp_ctx* c, int B, const std::vector<int>& parent, cons
       cstart[parent[v] + 1]++;
     }
     m[v][v >> 6] |= 1ull << (v & 63);
-    if (anchor[v] && k > 0) pbase[v] = N + k * n_anchor++;
+    if (anchor[v] && k > 0) pbase[v] = N + n_anchor++;   // step 1; step i is n_anchor further per step
   }
   for (int v = 0; v < N; ++v) cstart[v + 1] += cstart[v];
   {
@@ -457,21 +465,21 @@ firp_status upload_tree(firp_ctx* c, int B, const std::vector<int>& parent, cons
       pos[r] = depth[v];
       std::copy(m[v].begin(), m[v].end(), mask.begin() + (size_t)r * FIRP_MASK_WORDS);
     }
-    int a_idx = 0;
     for (int v = 0; v < N; ++v) {
       if (pbase[v] < 0) continue;
+      const int a_idx = pbase[v] - N;
       psrc[b * n_anchor + a_idx] = b * N + v;
       std::vector<unsigned long long> mm = m[v];
-      for (int i = 1; i <= k; ++i) {
-        int loc = pbase[v] + i - 1;
-        int r = B * N + b * P + (loc - N);
-        mm[loc >> 6] |= 1ull << (loc & 63);  // pseudo row i sees pseudo rows 1..i of its anchor
+      for (int i = 0; i < k; ++i) {
+        // local id N + i*A + a; global row behind the pseudo rows of all earlier steps
+        int loc = N + i * n_anchor + a_idx;
+        int r = B * N + i * (B * n_anchor) + b * n_anchor + a_idx;
+        mm[loc >> 6] |= 1ull << (loc & 63);  // pseudo row i sees the earlier pseudo rows of its anchor
         seq[r] = b;
         local[r] = loc;
-        pos[r] = depth[v] + i;
+        pos[r] = depth[v] + i + 1;
         std::copy(mm.begin(), mm.end(), mask.begin() + (size_t)r * FIRP_MASK_WORDS);
       }
-      ++a_idx;
     }
   }
   hipStream_t s = c->stream;
@@ -576,7 +584,7 @@ firp_status run_step(firp_ctx* c, const firp_tree* tree, const int32_t* node_tok
     inj = c->injected;
   }
   launch_fill_tokens(c->st, tree_tab(c, N, P), B, inj, s);
-  st = forward(c, B, B * N, B * T, B * n_anchor, N, T, B * N, true, ctx_max);
+  st = forward(c, B, N, n_anchor, true, ctx_max);
   if (st != FIRP_OK) return st;
   launch_verify_select(c->st, tree_tab(c, N, P), B, s);
   launch_kv_compact(kv_view(c, 0), c->kv_layer_stride, c->d.n_layers, B, c->st, c->dtype, s);
@@ -617,6 +625,19 @@ size_t firp_workspace_bytes(const firp_model_desc* desc, int32_t k) {
 firp_status firp_init(firp_ctx** out, const firp_model_desc* desc, const firp_weights* w,
                       const void* const* proj_w, const void* const* proj_b, int32_t layer_l, int32_t k,
                       void* workspace, size_t workspace_bytes, void* hip_stream) {
+  int32_t layers[FIRP_MAX_K];
+  for (int i = 0; i < FIRP_MAX_K; ++i) layers[i] = layer_l;
+  if (desc && (layer_l < 0 || layer_l > desc->n_layers)) {
+    if (out) *out = nullptr;
+    g_init_error = "layer_l outside [0, n_layers]";
+    return FIRP_EINVAL;
+  }
+  return firp_init_layers(out, desc, w, proj_w, proj_b, layers, k, workspace, workspace_bytes, hip_stream);
+}
+
+firp_status firp_init_layers(firp_ctx** out, const firp_model_desc* desc, const firp_weights* w,
+                             const void* const* proj_w, const void* const* proj_b, const int32_t* layers,
+                             int32_t k, void* workspace, size_t workspace_bytes, void* hip_stream) {
   auto bad = [&](firp_status code, const std::string& m) {
     g_init_error = m;
     return code;
@@ -625,7 +646,11 @@ firp_status firp_init(firp_ctx** out, const firp_model_desc* desc, const firp_we
   *out = nullptr;
   std::string why;
   if (!desc_ok(desc, k, why)) return bad(FIRP_EINVAL, why);
-  if (layer_l < 0 || layer_l > desc->n_layers) return bad(FIRP_EINVAL, "layer_l outside [0, n_layers]");
+  if (k > 0 && !layers) return bad(FIRP_EINVAL, "layers is NULL with k > 0");
+  for (int i = 0; i < k; ++i) {
+    if (layers[i] < 0 || layers[i] > desc->n_layers) return bad(FIRP_EINVAL, "a prediction layer is outside [0, n_layers]");
+    if (i > 0 && layers[i] < layers[i - 1]) return bad(FIRP_EINVAL, "prediction layers must not decrease");
+  }
   if (!w || !w->embed || !w->wq || !w->wk || !w->wv || !w->wo || !w->w_gate || !w->w_up || !w->w_down ||
       !w->norm_attn || !w->norm_mlp || !w->norm_final || !w->lm_head)
     return bad(FIRP_EINVAL, "a weight pointer is NULL");
@@ -642,7 +667,7 @@ firp_status firp_init(firp_ctx** out, const firp_model_desc* desc, const firp_we
   if (((uintptr_t)workspace) & 255) return bad(FIRP_EINVAL, "workspace is not 256-byte aligned");
   firp_ctx* c = new firp_ctx;
   setup_geometry(c, desc, k);
-  c->l = layer_l;
+  c->tl.assign(layers, layers + k);
   size_t need = carve(c, (char*)workspace);
   if (workspace_bytes < need) {
     delete c;
@@ -755,7 +780,7 @@ firp_status firp_prefill(firp_ctx* c, int32_t batch, const int32_t* tokens, cons
     while (done < todo) {
       int n = std::min(C, todo - done);
       HIPCHK(hipMemcpyAsync(c->st.tok, tk + done, n * sizeof(int), hipMemcpyHostToDevice, s));
-      firp_status st = forward(c, 1, n, n, 0, n, n, n, false, done);
+      firp_status st = forward(c, 1, n, 0, false, done);
       if (st != FIRP_OK) return st;
       launch_advance_by(c->st.p0, b, n, s);
       HIPCHK(hipStreamSynchronize(s));  // the token staging buffer is reused by the next chunk
@@ -817,8 +842,12 @@ firp_status firp_debug_last_logits(firp_ctx* c, float* logits, int32_t* n_rows) 
   HIPCHK(hipStreamSynchronize(c->stream));
   for (int b = 0; b < B; ++b) {
     HIPCHK(hipMemcpy(logits + ((size_t)b * T) * V, c->logits + ((size_t)b * N) * V, (size_t)N * V * sizeof(float), hipMemcpyDeviceToHost));
-    if (P)
-      HIPCHK(hipMemcpy(logits + ((size_t)b * T + N) * V, c->logits + ((size_t)B * N + (size_t)b * P) * V, (size_t)P * V * sizeof(float), hipMemcpyDeviceToHost));
+    // pseudo rows: step by step, inside a step sequence by sequence; handed out per sequence
+    const int A = c->k > 0 ? P / c->k : 0;
+    for (int i = 0; i < c->k && A > 0; ++i)
+      HIPCHK(hipMemcpy(logits + ((size_t)b * T + N + (size_t)i * A) * V,
+                       c->logits + ((size_t)B * N + (size_t)i * B * A + (size_t)b * A) * V, (size_t)A * V * sizeof(float),
+                       hipMemcpyDeviceToHost));
   }
   *n_rows = T;
   return FIRP_OK;

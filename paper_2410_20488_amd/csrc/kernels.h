@@ -24,9 +24,11 @@ struct TreeTab {
   const int* rank;
   const int* child_start; // CSR over children, [N+1]
   const int* child_list;  // [N-1]
-  const int* pseudo_base; // local row of the first pseudo row of node v, or -1
+  const int* pseudo_base; // local row of the first pseudo row (step 1) of node v, or -1; the
+                          // row of step i is n_anchor further per step
   int n_nodes;
-  int n_pseudo;           // pseudo rows per sequence
+  int n_pseudo;           // pseudo rows per sequence (k * n_anchor)
+  int n_anchor;           // anchors per sequence
 };
 
 // Per-sequence decoding state (device).
@@ -67,7 +69,8 @@ void launch_swiglu(const Partial& gate_up, const RowScale& rs, int rows, int d_f
 void launch_gather_rows(const float* x, const int* src_rows, int rows, int d, const Act& out,
                         bool split, hipStream_t s);
 // ... and scatter the maps' outputs (+ bias) to the pseudo rows: y holds `k_in_y` maps side by
-// side starting with map i0 (all k of them in one projection, or one map per projection).
+// side starting with map i0; anchor row g of map i goes to row first_pseudo_row +
+// i * n_anchor_rows + g (pseudo rows are ordered step by step).
 struct PseudoBias {
   const void* b[8];  // per map, nullptr = none
 };
@@ -96,13 +99,13 @@ void launch_attention_simple(const Act& q, bool split, int rows, int n_q_heads, 
 bool attention_mfma_supported(int head_dim, int dtype);
 size_t attention_mfma_scratch_floats(int rows, int n_q_heads, int head_dim);
 void launch_attention_mfma(const bf16* q_frag, int rows, int n_q_heads, int B, int n_real_per_seq,
-                           int n_pseudo_per_seq, const RowTab& rt, const int* p0, int max_ctx_now,
+                           int n_pseudo_per_seq, int n_anchor_per_seq, const RowTab& rt, const int* p0, int max_ctx_now,
                            const KvView& kv, float* scratch, const Act& out, hipStream_t s);
 // Its operand producer (replaces launch_rope_kv on this path): q as MFMA fragments in q_frag
 // (attention_q_frag_elems bf16 elements), K and V^T into the cache.
 size_t attention_q_frag_elems(int rows, int max_batch, int n_q_heads, int head_dim);
 void launch_rope_kv_tiles(const Partial& qkv, const RowScale& rs, int n_q_heads, int B, int n_real_per_seq,
-                          int n_pseudo_per_seq, const int* p0, const float2* tab, bf16* q_frag, const KvView& kv,
+                          int n_pseudo_per_seq, int n_anchor_per_seq, const int* p0, const float2* tab, bf16* q_frag, const KvView& kv,
                           hipStream_t s);
 
 // plain tiled projection: y[S=1][rows][n] = x_f32[rows][K] . W[n][K]^T

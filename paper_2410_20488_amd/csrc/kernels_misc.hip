@@ -252,11 +252,11 @@ template <typename BT>
 __global__ void k_scatter_pseudo(Partial y, int d, int k, int i0, int k_in_y, PseudoBias bias, float* x,
                                  int first_pseudo_row) {
   const int g = blockIdx.x, i = i0 + blockIdx.y;
-  float* xr = x + (size_t)(first_pseudo_row + g * k + i) * d;
+  float* xr = x + (size_t)(first_pseudo_row + i * (int)gridDim.x + g) * d;
   const BT* bi = (const BT*)bias.b[i];
   const int c = blockIdx.z * blockDim.x + threadIdx.x;
   if (c >= d) return;
-  float v = partial_sum(y, (size_t)g * y.ld + (size_t)(k_in_y > 1 ? i : 0) * d + c);
+  float v = partial_sum(y, (size_t)g * y.ld + (size_t)blockIdx.y * d + c);
   if (bi) v += to_f32(bi[c]);
   xr[c] = v;
 }
@@ -441,8 +441,13 @@ __global__ void k_verify_select(SeqState st, TreeTab tt) {
   __syncthreads();
   int pb = tt.pseudo_base[s_cur];
   if (pb >= 0 && st.k > 0) {
-    const int* src = st.top + ((size_t)b * tt.n_pseudo + (pb - N)) * st.b_max;
-    for (int e = threadIdx.x; e < st.k * st.b_max; e += blockDim.x) st.drafts[(size_t)b * st.k * st.b_max + e] = src[e];
+    // pseudo rows are ordered step by step: step i of anchor a of sequence b is pseudo row
+    // i * (B * A) + b * A + a
+    const int B = gridDim.x, A = tt.n_anchor, a = pb - N;
+    for (int e = threadIdx.x; e < st.k * st.b_max; e += blockDim.x) {
+      const int i = e / st.b_max, j = e - i * st.b_max;
+      st.drafts[(size_t)b * st.k * st.b_max + e] = st.top[((size_t)i * B * A + (size_t)b * A + a) * st.b_max + j];
+    }
   }
 }
 

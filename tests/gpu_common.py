@@ -17,7 +17,7 @@ def make_engine(cfg: synth.ModelConfig, weights, *, max_ctx: int, max_batch=1, m
                        n_kv_heads=cfg.n_kv_heads, head_dim=cfg.head_dim, d_ffn=cfg.d_ffn, vocab=cfg.vocab,
                        rms_eps=cfg.rms_eps, rope_base=cfg.rope_base, dtype=cfg.dtype, weights=weights,
                        firp_layer=cfg.firp_layer, k=cfg.k, max_ctx=max_ctx, max_batch=max_batch,
-                       max_nodes=max_nodes, max_rows=max_rows, b_max=b_max)
+                       max_nodes=max_nodes, max_rows=max_rows, b_max=b_max, firp_layers=cfg.firp_layers)
     if gemm is not None:
         e.set_option("gemm", gemm)
     return e
@@ -136,9 +136,8 @@ def run_lockstep(cfg, weights_gpu, tree: synth.Tree, *, prompt_len: int, n_steps
             d, valid = eng.drafts()
             assert bool(valid[0]) == (r.drafts is not None), f"step {step}: drafts validity"
             if r.drafts is not None and d[0].tolist() != r.drafts:
-                first = tree_first_pseudo = r.rows.n_nodes + [a for a, _ in r.rows.pseudo_of].index(r.path[-1])
                 for i in range(cfg.k):
-                    row = ref[first + i]
+                    row = ref[r.rows.pseudo_row(r.path[-1], i + 1)]
                     g = d[0][i].tolist()
                     assert len(set(g)) == len(g)
                     for a, b in zip(g[:-1], g[1:]):

@@ -96,6 +96,28 @@ def test_init_argument_errors(lib):
     h.close()
 
 
+def test_init_layers_argument_errors(lib):
+    """One prediction layer per step: entries inside [0, n_layers] and not decreasing."""
+    h = _HostCtx(lib, k=3)
+    nbytes = lib.firp_workspace_bytes(C.byref(h.desc), 3)
+    L = h.desc.n_layers
+
+    def init(layers):
+        arr = (C.c_int32 * 3)(*layers) if layers is not None else None
+        return lib.firp_init_layers(C.byref(h.ctx), C.byref(h.desc), C.byref(h.w),
+                                    C.cast(h.pw, C.POINTER(C.c_void_p)), None, arr, 3, 0x100000, nbytes, None)
+
+    assert init(None) == -1 and b"layers" in lib.firp_last_error(None)
+    assert init([0, 1, L + 1]) == -1 and b"outside" in lib.firp_last_error(None)
+    assert init([-1, 0, 1]) == -1
+    assert init([2, 1, 2]) == -1 and b"decrease" in lib.firp_last_error(None)
+    assert not h.ctx
+    assert init([0, 1, L]) == 0 and h.ctx
+    h.close()
+    assert init([1, 1, 1]) == 0 and h.ctx
+    h.close()
+
+
 def test_state_and_prefill_errors_leave_no_device_work(lib):
     h = _HostCtx(lib)
     assert h.init() == 0

@@ -67,6 +67,23 @@ def test_tiny_gqa_mfma_random_tree(dev, progress):
     run_lockstep(cfg, w, tree, prompt_len=150, n_steps=9, tol=2e-2, progress=progress)
 
 
+@pytest.mark.parametrize("name,layers,gemm,tol", [("tiny", (1, 2, 3), None, 1e-4), ("tiny", (0, 2, 4), None, 1e-4),
+                                                  ("tiny", (2, 2, 3), None, 1e-4), ("tiny_bf16", (1, 2, 3), 1, 2e-2),
+                                                  ("tiny_bf16", (0, 3, 3), 1, 2e-2)])
+@pytest.mark.parametrize("anchors", ["root", "all"])
+def test_one_prediction_layer_per_step(dev, progress, name, layers, gemm, tol, anchors):
+    """Pseudo hidden state i enters at its own layer t_i (Training stage; Setup uses three different
+    layers): the step's row count grows through the stack."""
+    import dataclasses
+    cfg = dataclasses.replace(synth.CONFIGS[name], firp_layers=layers)
+    w = synth.make_weights(cfg, dev, with_bias=True)
+    tree = synth.full_tree((3, 2, 2), anchors)
+    rep, eng, orc = run_lockstep(cfg, w, tree, prompt_len=41, n_steps=8, tol=tol, gemm=gemm, progress=progress)
+    if cfg.dtype == "f32":
+        assert rep.tie_ambiguous == 0
+    compare_cache(eng, orc, cfg)
+
+
 def test_7b_widths_4_layers_full_tree(dev, progress):
     """LLaMA-2-7B widths, 4 layers (the oracle finishes in seconds), the 41-node 4/3/2 tree."""
     cfg = synth.scaled_config(synth.CONFIGS["7b"], 4, 2)
