@@ -32,7 +32,9 @@ def algorithmic_bytes(cfg, n_nodes: int, t_hi: int, ctx: int) -> float:
     kv_row = 2 * cfg.n_kv_heads * cfg.head_dim * e                 # K and V of one row, one layer
     weights = e * (cfg.n_layers * cfg.layer_params() + cfg.vocab * cfg.d_model + cfg.k * cfg.d_model ** 2)
     kv_sweep = ctx * kv_row * cfg.n_layers
-    step_rows = 2 * kv_row * (n_nodes * cfg.firp_layer + t_hi * (cfg.n_layers - cfg.firp_layer))
+    n_anchor = (t_hi - n_nodes) // max(cfg.k, 1)
+    step_rows = 2 * kv_row * sum(n_nodes + n_anchor * sum(1 for t in cfg.layers if t <= layer)
+                                 for layer in range(cfg.n_layers))
     return float(weights + kv_sweep + step_rows)
 
 
@@ -84,6 +86,9 @@ def main() -> int:
     ap.add_argument("--config", default="13b", choices=["13b", "7b", "tiny_bf16"])
     ap.add_argument("--prompt", type=int, default=0, help="prompt length (default: the configuration's)")
     ap.add_argument("--anchors", default="root", choices=["root", "all"])
+    ap.add_argument("--firp-layers", default="",
+                    help="comma-separated prediction layer per step (e.g. 25,30,35: the paper's 13B setting); "
+                         "default: the benchmark configuration's single layer")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a plain 1 GiB device copy three times (reference for scaling the "
@@ -111,6 +116,10 @@ def main() -> int:
         print(json.dumps({"copy_bytes": 1 << 30, "copies": 3}))
         return 0
     cfg = synth.CONFIGS[args.config]
+    if args.firp_layers:
+        import dataclasses
+        cfg = dataclasses.replace(cfg, firp_layers=tuple(int(t) for t in args.firp_layers.split(",")))
+        assert len(cfg.firp_layers) == cfg.k
     tree = synth.workload_tree(args.config, args.anchors)
     prompt_len = args.prompt or {"13b": 1024, "7b": 512, "tiny_bf16": 64}[args.config]
     t_start = time.time()
@@ -155,7 +164,7 @@ def main() -> int:
         "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": False,
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"LLaMA-2-{args.config.upper()}-shaped decoder, bf16 random-init, k={cfg.k} maps at "
-                               f"layer {cfg.firp_layer}, batch 1, prompt {prompt_len} uniform-random tokens, "
+                               f"layer {cfg.firp_layer if cfg.firp_layers is None else list(cfg.firp_layers)}, batch 1, prompt {prompt_len} uniform-random tokens, "
                                f"{tree.n_nodes}-node draft tree, anchors={args.anchors} (T_hi={t_hi}), "
                                f"ctx {ctx_first}->{ctx_last}"},
         "step_algorithmic_GB": round(step_bytes / 1e9, 3),

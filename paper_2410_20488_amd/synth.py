@@ -141,6 +141,7 @@ CONFIGS: Dict[str, ModelConfig] = {
 def scaled_config(base: ModelConfig, n_layers: int, firp_layer: int, name: Optional[str] = None,
                   **kw) -> ModelConfig:
     """Same widths as `base`, fewer layers: a parity case the oracle finishes quickly."""
+    kw.setdefault("firp_layers", None)   # per-step layers of the full model do not carry over
     return dataclasses.replace(base, name=name or f"{base.name}_L{n_layers}", n_layers=n_layers,
                                firp_layer=firp_layer, **kw)
 
