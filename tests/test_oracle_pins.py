@@ -368,3 +368,31 @@ def test_config1_fp32_32_steps_lossless():
     o64 = make_oracle(cfg, w, dtype=F64)
     want = o64.greedy(prompt, 12)
     assert got[:12] == want
+
+
+def test_map_shapes_reproduce_the_printed_draft_parameter_counts():
+    """Training stage defines one d x d matrix and one bias of d per prediction step; Table 1
+    prints the resulting extra parameters (0.08 B for the 13B models, 0.05 B for the 7B models,
+    k = 3).  The oracle insists on exactly these shapes, and the benchmark configurations'
+    map sizes round to the printed values."""
+    import os
+    rows = []
+    with open(os.path.join(os.path.dirname(__file__), "golden", "draft_parameter_counts.txt")) as f:
+        for line in f:
+            if line.strip() and not line.startswith("#"):
+                name, k, d, printed = line.split()
+                rows.append((name, int(k), int(d), float(printed)))
+    assert len(rows) == 4
+    for name, k, d, printed in rows:
+        assert round(k * (d * d + d) / 1e9, 2) == printed, name
+    for cfg_name, d in (("13b", 5120), ("7b", 4096)):
+        cfg = synth.CONFIGS[cfg_name]
+        printed = {r[2]: r[3] for r in rows}[d]
+        assert cfg.d_model == d and cfg.k == 3
+        assert round(cfg.k * (cfg.d_model ** 2 + cfg.d_model) / 1e9, 2) == printed
+    # the oracle refuses maps of any other shape
+    w = synth.make_weights(MICRO, "cpu", with_bias=True, std=0.08)
+    w_bad = dict(w)
+    w_bad["proj_w"] = [p[:, :-1] for p in w["proj_w"]]
+    with pytest.raises(AssertionError):
+        make_oracle(MICRO, w_bad)
