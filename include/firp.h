@@ -173,8 +173,25 @@ firp_status firp_step_with_candidates(firp_ctx *ctx, const firp_tree *tree,
  * firp_step does first); n_rows (may be NULL) receives N + k*|A|.  Touches no device. */
 firp_status firp_check_tree(firp_ctx *ctx, const firp_tree *tree, int32_t *n_rows);
 
-/* Logits of the last step, HOST [batch][T_hi][V] fp32, rows in step order (tree nodes, then
- * for each anchor in ascending node id its k pseudo rows).  n_rows receives T_hi. */
+/*
+ * Draft-tree topology for a node budget (Experiment / Setup: the best tree structure is searched
+ * for every budget of tree nodes).  accept: HOST [k][b] acceptance rates in [0, 1]: accept[i][r]
+ * is the rate at which the rank-r candidate of prediction step i+1 is the target's token given
+ * that its parent was accepted.  Under greedy verification a node is accepted with the product
+ * of the rates along its path, and a step yields 1 + the sum of these products tokens on
+ * average; the function returns the tree of at most n_nodes nodes (root included) that
+ * maximises this (ties: shallower node first, then the smaller rank path), nodes in an order
+ * firp_step accepts (parent before child).  parent / rank: HOST arrays of n_nodes entries;
+ * n_out receives the node count (smaller than n_nodes when fewer nodes have a non-zero
+ * product); expected_tokens (may be NULL) receives the objective.  Host only, no device work.
+ */
+firp_status firp_build_tree(const float *accept, int32_t k, int32_t b, int32_t n_nodes,
+                            int32_t *parent, int32_t *rank, int32_t *n_out,
+                            double *expected_tokens);
+
+/* Logits of the last step, HOST [batch][T_hi][V] fp32, rows in step order: the tree nodes, then
+ * pseudo row 1 of every anchor (ascending node id), then pseudo row 2 of every anchor, ...
+ * n_rows receives T_hi. */
 firp_status firp_debug_last_logits(firp_ctx *ctx, float *logits, int32_t *n_rows);
 
 /* Node ids of the last accepted path, HOST [batch][FIRP_MAX_K + 1]. */

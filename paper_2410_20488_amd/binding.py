@@ -65,6 +65,8 @@ def load_library() -> C.CDLL:
                                  C.POINTER(vp), C.c_int32, C.c_int32, vp, C.c_size_t, vp]),
         "firp_init_layers": (C.c_int, [C.POINTER(vp), C.POINTER(ModelDesc), C.POINTER(Weights), C.POINTER(vp),
                                         C.POINTER(vp), i32p, C.c_int32, vp, C.c_size_t, vp]),
+        "firp_build_tree": (C.c_int, [C.POINTER(C.c_float), C.c_int32, C.c_int32, C.c_int32, i32p, i32p, i32p,
+                                       C.POINTER(C.c_double)]),
         "firp_prefill": (C.c_int, [vp, C.c_int32, i32p, i32p, i32p]),
         "firp_step": (C.c_int, [vp, C.POINTER(Tree), i32p, i32p]),
         "firp_reset": (C.c_int, [vp]),
@@ -90,7 +92,7 @@ def load_library() -> C.CDLL:
     return lib
 
 
-EXPORTED = ["firp_workspace_bytes", "firp_init", "firp_init_layers", "firp_prefill", "firp_step", "firp_reset", "firp_destroy",
+EXPORTED = ["firp_workspace_bytes", "firp_init", "firp_init_layers", "firp_build_tree", "firp_prefill", "firp_step", "firp_reset", "firp_destroy",
             "firp_last_error", "firp_step_with_candidates", "firp_check_tree", "firp_debug_last_logits", "firp_debug_last_path",
             "firp_get_drafts", "firp_get_ctx_len", "firp_debug_read_cache", "firp_set_option", "firp_get_gemm_timing",
             "firp_gemm_workspace_bytes", "firp_debug_gemm"]
@@ -102,6 +104,24 @@ def _i32(a) -> np.ndarray:
 
 def _p(a: np.ndarray, ty=C.c_int32):
     return a.ctypes.data_as(C.POINTER(ty))
+
+
+def build_tree(accept, n_nodes: int):
+    """Best draft tree of at most `n_nodes` nodes for acceptance rates accept[k][b] (host only).
+    Returns (parent, rank, expected tokens per step)."""
+    lib = load_library()
+    a = np.ascontiguousarray(np.asarray(accept, dtype=np.float32))
+    k, b = (a.shape if a.ndim == 2 else (0, 1))
+    parent = np.zeros(n_nodes, dtype=np.int32)
+    rank = np.zeros(n_nodes, dtype=np.int32)
+    n_out = C.c_int32(0)
+    expect = C.c_double(0.0)
+    rc = lib.firp_build_tree(a.ctypes.data_as(C.POINTER(C.c_float)), k, b, n_nodes, _p(parent), _p(rank),
+                             C.byref(n_out), C.byref(expect))
+    if rc != 0:
+        raise FirpError(rc, "firp_build_tree: invalid argument")
+    n = n_out.value
+    return parent[:n].tolist(), rank[:n].tolist(), expect.value
 
 
 def make_tree(parent: Sequence[int], rank: Sequence[int], anchor: Optional[Sequence[int]]):
