@@ -25,7 +25,9 @@ What it computes (paper: Methodology / FIRP, Inference stage, Tree attention; Eq
   no child does: the accepted path S is the longest one, and `len(S)+1` tokens come out;
 * the next draft tree is read off the pseudo rows of the node that ends S: level i gets the
   top-b ids of pseudo row i (ties to the lower id), node v carries `drafts[level-1][rank]`;
-* commit: K and V of the accepted path's nodes are appended to the cache.
+* commit: K and V of the accepted path's nodes are appended to the cache;
+* the forward pass of the Training stage (Eq. 3-4): the 2n-row sequence of hidden and pseudo
+  hidden states with its mask and position ids, and the KL loss (`train_forward`).
 
 Arithmetic is done in `dtype` (fp32 by default as the build's contract names an fp32 oracle;
 fp64 for the pins).  Weights are whatever bit patterns the caller hands over, widened
@@ -36,7 +38,8 @@ Pins (tests/test_oracle_pins.py): the decoder against the HuggingFace LLaMA impl
 the paper builds on and against torch's library attention / rms_norm; RoPE's relative-
 position property; tree attention against brute-force per-path causal runs; pseudo rows
 against a brute-force chain with hand-inserted rows; losslessness against cache-free
-sequential greedy decoding; forced-acceptance cases; commit == prefill.
+sequential greedy decoding; forced-acceptance cases; commit == prefill; the training forward
+against per-position causal chains and the library KL routine.
 """
 from __future__ import annotations
 
@@ -256,6 +259,43 @@ class FirpOracle:
             out.append(t)
             seq.append(t)
         return out
+
+    # -- Training stage, forward only ---------------------------------------------------------
+    def train_forward(self, tokens: Sequence[int], step: int):
+        """Forward pass of the Training stage for prediction step `step` (1-based) on one
+        sequence X_1..X_n, from an empty context; the KL loss of Eq. 4 and its terms.
+
+        The n hidden states entering layer t_step are mapped (Eq. 3) to n pseudo hidden states
+        and appended: rows [h_1..h_n, h~_1..h~_n].  h~_j stands for position j + step: it sees
+        h_1 .. h_{j+step-1} and itself (the rows that exist: at most h_n) and carries position
+        id j + step; the real rows stay causal among themselves.  All 2n rows pass the
+        remaining layers and the lm-head; loss = sum_{q=1}^{n-step} KL(P~_q, P_{q+step}), with
+        KL(A, B) = sum_t A_t (log A_t - log B_t).
+        Returns (loss, kl[n - step], logits[2n, V])."""
+        n, i = len(tokens), int(step)
+        assert 1 <= i <= self.k and n > i
+        t_i = self.layers[i - 1]
+        empty = torch.zeros(0, self.Hkv, self.dh, dtype=self.dtype)
+        x = self._embed(tokens)
+        causal = torch.tril(torch.ones(n, n, dtype=torch.bool))
+        for layer in range(t_i):
+            x, _, _ = self._layer(layer, x, torch.arange(n), empty, empty, causal)
+        pseudo = x @ self._W("proj_w", i - 1).T
+        if self.w.get("proj_b") is not None:
+            pseudo = pseudo + self._W("proj_b", i - 1)
+        x = torch.cat([x, pseudo])
+        pos = torch.cat([torch.arange(n), torch.arange(n) + i])      # 0-based position ids
+        vis = torch.zeros(2 * n, 2 * n, dtype=torch.bool)
+        vis[:n, :n] = causal
+        for j in range(n):                                           # 0-based j: pseudo row of h_{j+1}
+            vis[n + j, : min(j + i, n)] = True                       # h_1 .. h_{j+1+step-1}
+            vis[n + j, n + j] = True
+        for layer in range(t_i, self.L):
+            x, _, _ = self._layer(layer, x, pos, empty, empty, vis)
+        logits = self._logits(x)
+        logp = torch.log_softmax(logits, dim=-1)
+        kl = torch.stack([(logp[n + q].exp() * (logp[n + q] - logp[q + i])).sum() for q in range(n - i)])
+        return float(kl.sum()), kl, logits
 
     # -- the FIRP step ---------------------------------------------------------------------
     def prefill(self, tokens: Sequence[int]) -> int:

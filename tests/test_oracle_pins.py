@@ -396,3 +396,63 @@ def test_map_shapes_reproduce_the_printed_draft_parameter_counts():
     w_bad["proj_w"] = [p[:, :-1] for p in w["proj_w"]]
     with pytest.raises(AssertionError):
         make_oracle(MICRO, w_bad)
+
+
+@pytest.mark.parametrize("step,layers", [(1, None), (2, None), (2, (0, 2)), (1, (3, 3))])
+def test_training_forward_against_per_position_chains(step, layers):
+    """Training stage: pseudo row q is the stand-in for position q + step, so its distribution must
+    equal what a plain causal chain over X_1..X_{q+step-1} gives when one extra row, W h_q + b,
+    is inserted at the prediction layer at position q + step (seeing all of them and itself);
+    P_{q+step} is the plain causal pass; the loss is the sum of KL(P~_q, P_{q+step}) over q
+    (Eq. 4), here with the library's KL routine."""
+    cfg = MICRO if layers is None else dataclasses.replace(MICRO, firp_layers=layers)
+    o, w = _micro(cfg=cfg)
+    toks = synth.prompt_tokens(91, 9, cfg.vocab).tolist()
+    n = len(toks)
+    loss, kl, logits = o.train_forward(toks, step)
+    assert logits.shape == (2 * n, cfg.vocab) and kl.shape == (n - step,)
+    brute = make_oracle(cfg, w, dtype=F64)
+    plain = brute.causal_forward(toks)
+    assert (logits[:n] - plain).abs().max() < 1e-9            # real rows are untouched by pseudo rows
+    empty = torch.zeros(0, cfg.n_kv_heads, cfg.head_dim, dtype=F64)
+    t_i = cfg.layers[step - 1]
+    total = 0.0
+    for q in range(n):                                          # 0-based: pseudo row of X_{q+1}
+        m = min(q + step, n)                                    # real rows it may see
+        x = brute._embed(toks[:m])
+        for layer in range(t_i):
+            x, _, _ = brute._layer(layer, x, torch.arange(m), empty, empty,
+                                   torch.tril(torch.ones(m, m, dtype=torch.bool)))
+        extra = w["proj_w"][step - 1].double() @ x[q] + w["proj_b"][step - 1].double()
+        x = torch.cat([x, extra[None]])
+        pos = torch.cat([torch.arange(m), torch.tensor([q + step])])
+        for layer in range(t_i, cfg.n_layers):
+            x, _, _ = brute._layer(layer, x, pos, empty, empty, torch.tril(torch.ones(m + 1, m + 1, dtype=torch.bool)))
+        ref = brute._logits(x)[-1]
+        assert (logits[n + q] - ref).abs().max() < 1e-9, f"pseudo row {q}"
+        if q < n - step:
+            want = torch.nn.functional.kl_div(torch.log_softmax(plain[q + step], -1), torch.log_softmax(ref, -1),
+                                              reduction="sum", log_target=True)
+            assert abs(float(kl[q]) - float(want)) < 1e-9
+            total += float(want)
+    assert abs(loss - total) < 1e-8 and loss > 0.0
+
+
+def test_training_loss_vanishes_when_the_pseudo_state_is_the_true_one():
+    """Closed form: with the map at the last layer boundary (t = L) replaced by the exact shift
+    h~_q = h_{q+1} nothing but the lm-head follows, so P~_q = P_{q+1} and the loss is 0.  A
+    linear map cannot shift rows, so the shifted rows are planted through the bias of a
+    one-token-per-row construction: here n = 2 and W = 0, b = h_2."""
+    cfg = dataclasses.replace(MICRO, firp_layers=(MICRO.n_layers, MICRO.n_layers))
+    o, w = _micro(cfg=cfg)
+    toks = synth.prompt_tokens(92, 2, cfg.vocab).tolist()
+    x = o._embed(toks)
+    empty = torch.zeros(0, cfg.n_kv_heads, cfg.head_dim, dtype=F64)
+    for layer in range(cfg.n_layers):
+        x, _, _ = o._layer(layer, x, torch.arange(2), empty, empty, torch.tril(torch.ones(2, 2, dtype=torch.bool)))
+    w2 = dict(w)
+    w2["proj_w"] = [torch.zeros_like(p) for p in w["proj_w"]]
+    w2["proj_b"] = [x[1].clone() for _ in w["proj_b"]]
+    o2 = make_oracle(cfg, w2, dtype=F64)
+    loss, kl, _ = o2.train_forward(toks, 1)
+    assert kl.shape == (1,) and abs(loss) < 1e-12
