@@ -152,6 +152,21 @@ firp_status firp_prefill(firp_ctx *ctx, int32_t batch, const int32_t *tokens,
 firp_status firp_step(firp_ctx *ctx, const firp_tree *tree, int32_t *accepted,
                       int32_t *n_accepted);
 
+/*
+ * Forward pass of the Training stage for prediction step `step` (1..k) on one sequence of n
+ * tokens (Training stage, Eq. 3-4), forward only: the n hidden states entering the step's
+ * prediction layer are mapped to n pseudo hidden states and appended; pseudo row j (the stand-in
+ * for position j + step) sees hidden states 1 .. j + step - 1 and itself and carries position id
+ * j + step; all 2n rows pass the remaining layers and the lm-head.
+ *   loss: HOST, receives sum_{q=1}^{n-step} KL(P~_q, P_{q+step}), KL(A,B) = sum_t A_t log(A_t/B_t);
+ *   kl:   HOST [n - step] or NULL, the terms of the sum.
+ * Needs a context that holds no sequence (fresh, or after firp_reset) and 2n <= max_rows; uses
+ * sequence 0's cache slots as scratch and leaves the context without sequences.  The 2n rows
+ * of logits can be read with firp_debug_last_logits afterwards.
+ */
+firp_status firp_train_forward(firp_ctx *ctx, const int32_t *tokens, int32_t n, int32_t step,
+                               double *loss, float *kl);
+
 /* Drop all sequences (the cache becomes empty); weights and workspace stay. */
 firp_status firp_reset(firp_ctx *ctx);
 

@@ -67,6 +67,8 @@ def load_library() -> C.CDLL:
                                         C.POINTER(vp), i32p, C.c_int32, vp, C.c_size_t, vp]),
         "firp_build_tree": (C.c_int, [C.POINTER(C.c_float), C.c_int32, C.c_int32, C.c_int32, i32p, i32p, i32p,
                                        C.POINTER(C.c_double)]),
+        "firp_train_forward": (C.c_int, [vp, i32p, C.c_int32, C.c_int32, C.POINTER(C.c_double),
+                                          C.POINTER(C.c_float)]),
         "firp_prefill": (C.c_int, [vp, C.c_int32, i32p, i32p, i32p]),
         "firp_step": (C.c_int, [vp, C.POINTER(Tree), i32p, i32p]),
         "firp_reset": (C.c_int, [vp]),
@@ -92,7 +94,7 @@ def load_library() -> C.CDLL:
     return lib
 
 
-EXPORTED = ["firp_workspace_bytes", "firp_init", "firp_init_layers", "firp_build_tree", "firp_prefill", "firp_step", "firp_reset", "firp_destroy",
+EXPORTED = ["firp_workspace_bytes", "firp_init", "firp_init_layers", "firp_build_tree", "firp_train_forward", "firp_prefill", "firp_step", "firp_reset", "firp_destroy",
             "firp_last_error", "firp_step_with_candidates", "firp_check_tree", "firp_debug_last_logits", "firp_debug_last_path",
             "firp_get_drafts", "firp_get_ctx_len", "firp_debug_read_cache", "firp_set_option", "firp_get_gemm_timing",
             "firp_gemm_workspace_bytes", "firp_debug_gemm"]
@@ -250,6 +252,15 @@ class Engine:
     def reset(self):
         self._check(self.lib.firp_reset(self.ctx))
         self.batch = 0
+
+    def train_forward(self, tokens: Sequence[int], step: int):
+        """Training-stage forward for prediction step `step`: (loss, kl[n - step])."""
+        t = _i32(list(tokens))
+        kl = np.zeros(len(t) - step, dtype=np.float32)
+        loss = C.c_double(0.0)
+        self._check(self.lib.firp_train_forward(self.ctx, _p(t), len(t), step, C.byref(loss), _p(kl, C.c_float)))
+        self.batch = 1
+        return loss.value, kl
 
     def last_logits(self) -> np.ndarray:
         """[batch][T_hi][V] fp32 of the last step."""

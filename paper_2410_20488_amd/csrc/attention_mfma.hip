@@ -69,9 +69,9 @@ __device__ __forceinline__ int global_row(const SeqRows& sr, int b, int local) {
 // wave reads whole rows of the partial sums in 16-byte pieces.
 template <int DH>
 __global__ __launch_bounds__(256) void k_rope_kv_tiles(Partial qkv, RowScale rs, int n_q_heads, SeqRows sr,
-                                                       int n_local, int n_tiles, const int* __restrict__ p0v,
-                                                       const float2* __restrict__ tab, bf16* __restrict__ q_frag,
-                                                       KvView kv) {
+                                                       int n_local, int n_tiles, int seq0,
+                                                       const int* __restrict__ p0v, const float2* __restrict__ tab,
+                                                       bf16* __restrict__ q_frag, KvView kv) {
   constexpr int TPH = 2 * DH, HPB = 256 / TPH, HALF = DH / 2, DS = DH / 32, CPR = DH / 8;  // chunks per row
   __shared__ unsigned short vt_lds[HPB][16][DH + 8];
   const int tile = blockIdx.x % n_tiles, b = blockIdx.x / n_tiles;
@@ -81,7 +81,8 @@ __global__ __launch_bounds__(256) void k_rope_kv_tiles(Partial qkv, RowScale rs,
   const int c = t % CPR, r16 = t / CPR;
   const int local = tile * 16 + r16;
   const bool valid = local < n_local && h < heads;
-  const int p0 = p0v[b];
+  const int bs = seq0 + b;   // sequence whose cache this launch works on (b counts inside the launch)
+  const int p0 = p0v[bs];
   if (valid) {
     const int row = global_row(sr, b, local);
     const size_t col = (size_t)row * qkv.ld + (size_t)h * DH + 4 * c;
@@ -133,7 +134,7 @@ __global__ __launch_bounds__(256) void k_rope_kv_tiles(Partial qkv, RowScale rs,
       }
     } else if (h < n_q_heads + Hkv) {
       const int hk = h - n_q_heads;
-      bf16* krow = (bf16*)kv.k + (size_t)b * kv.seq_stride + ((size_t)hk * kv.slots + (size_t)(p0 + local)) * DH;
+      bf16* krow = (bf16*)kv.k + (size_t)bs * kv.seq_stride + ((size_t)hk * kv.slots + (size_t)(p0 + local)) * DH;
       *(uint2*)(krow + 4 * c) = make_uint2(pack2_bf16(x1[0], x1[1]), pack2_bf16(x1[2], x1[3]));
       *(uint2*)(krow + 4 * c + HALF) = make_uint2(pack2_bf16(x2[0], x2[1]), pack2_bf16(x2[2], x2[3]));
     } else {
@@ -147,7 +148,7 @@ __global__ __launch_bounds__(256) void k_rope_kv_tiles(Partial qkv, RowScale rs,
   __syncthreads();
   if (h >= n_q_heads + Hkv && h < heads) {
     const int hv = h - n_q_heads - Hkv;
-    unsigned short* vt = (unsigned short*)kv.v + (size_t)b * kv.seq_stride + (size_t)hv * DH * kv.slots + p0 + tile * 16;
+    unsigned short* vt = (unsigned short*)kv.v + (size_t)bs * kv.seq_stride + (size_t)hv * DH * kv.slots + p0 + tile * 16;
     for (int idx = t; idx < DH * 16; idx += TPH) {
       const int dim = idx >> 4, rr = idx & 15;
       if (tile * 16 + rr < n_local) vt[(size_t)dim * kv.slots + rr] = vt_lds[hsel][rr][dim];
@@ -160,25 +161,25 @@ size_t attention_q_frag_elems(int rows, int max_batch, int n_q_heads, int head_d
 }
 
 void launch_rope_kv_tiles(const Partial& qkv, const RowScale& rs, int n_q_heads, int B, int n_real_per_seq,
-                          int n_pseudo_per_seq, int n_anchor_per_seq, const int* p0, const float2* tab, bf16* q_frag,
-                          const KvView& kv, hipStream_t s) {
+                          int n_pseudo_per_seq, int n_anchor_per_seq, int seq0, const int* p0, const float2* tab,
+                          bf16* q_frag, const KvView& kv, hipStream_t s) {
   const int n_local = n_real_per_seq + n_pseudo_per_seq, n_tiles = (n_local + 15) / 16;
   SeqRows sr{n_real_per_seq, std::max(1, n_anchor_per_seq), B * n_real_per_seq, B * n_anchor_per_seq};
   const int dh = kv.head_dim, heads = n_q_heads + 2 * kv.n_kv_heads, hpb = 128 / dh;
   dim3 g(B * n_tiles, (heads + hpb - 1) / hpb), blk(256);
   if (dh == 128)
-    hipLaunchKernelGGL(k_rope_kv_tiles<128>, g, blk, 0, s, qkv, rs, n_q_heads, sr, n_local, n_tiles, p0, tab, q_frag, kv);
+    hipLaunchKernelGGL(k_rope_kv_tiles<128>, g, blk, 0, s, qkv, rs, n_q_heads, sr, n_local, n_tiles, seq0, p0, tab, q_frag, kv);
   else if (dh == 64)
-    hipLaunchKernelGGL(k_rope_kv_tiles<64>, g, blk, 0, s, qkv, rs, n_q_heads, sr, n_local, n_tiles, p0, tab, q_frag, kv);
+    hipLaunchKernelGGL(k_rope_kv_tiles<64>, g, blk, 0, s, qkv, rs, n_q_heads, sr, n_local, n_tiles, seq0, p0, tab, q_frag, kv);
   else
-    hipLaunchKernelGGL(k_rope_kv_tiles<32>, g, blk, 0, s, qkv, rs, n_q_heads, sr, n_local, n_tiles, p0, tab, q_frag, kv);
+    hipLaunchKernelGGL(k_rope_kv_tiles<32>, g, blk, 0, s, qkv, rs, n_q_heads, sr, n_local, n_tiles, seq0, p0, tab, q_frag, kv);
 }
 
 template <int DH>
 __global__ __launch_bounds__(64 * NWAVES, 1) void k_attention_mfma(const bf16* __restrict__ q_frag,
                                                           int n_q_heads, SeqRows sr, int n_local,
                                                           const unsigned long long* __restrict__ row_mask,
-                                                          const int* __restrict__ p0v, KvView kv, int chunk,
+                                                          const int* __restrict__ p0v, int seq0, KvView kv, int chunk,
                                                           float* __restrict__ part_o, float* __restrict__ part_ml,
                                                           int splits) {
   constexpr int DS = DH / 32;       // k-steps of the score product
@@ -196,13 +197,14 @@ __global__ __launch_bounds__(64 * NWAVES, 1) void k_attention_mfma(const bf16* _
   // last block the launch geometry allows: the first fetches go out against this bound, before
   // the committed length has even arrived
   const int hard_last = (min(key_begin + chunk, kv.slots) - key_begin - 32) >> 5;
-  const int p0 = p0v[b];
+  const int bs = seq0 + b;   // sequence whose cache this launch reads (b counts inside the launch)
+  const int p0 = p0v[bs];
   const int n_keys = p0 + n_local;
   const int key_end = min(n_keys, key_begin + chunk);
   const int nb = key_end > key_begin ? (key_end - key_begin + 31) >> 5 : 0;   // blocks of this chunk
   const int last = nb - 1;
-  const bf16* Kb = (const bf16*)kv.k + (size_t)b * kv.seq_stride + (size_t)hk * kv.slots * DH;
-  const bf16* Vt = (const bf16*)kv.v + (size_t)b * kv.seq_stride + (size_t)hk * DH * kv.slots;
+  const bf16* Kb = (const bf16*)kv.k + (size_t)(seq0 + b) * kv.seq_stride + (size_t)hk * kv.slots * DH;
+  const bf16* Vt = (const bf16*)kv.v + (size_t)(seq0 + b) * kv.seq_stride + (size_t)hk * DH * kv.slots;
   const float sc = 1.4426950408889634f / sqrtf((float)DH);  // log2(e) / sqrt(dh)
   const float NEG = -__builtin_inff();
 
@@ -496,7 +498,7 @@ size_t attention_mfma_scratch_floats(int rows, int n_q_heads, int head_dim) {
 }
 
 void launch_attention_mfma(const bf16* q_frag, int rows, int n_q_heads, int B, int n_real_per_seq, int n_pseudo_per_seq,
-                           int n_anchor_per_seq, const RowTab& rt, const int* p0, int max_ctx_now, const KvView& kv, float* scratch,
+                           int n_anchor_per_seq, int seq0, const RowTab& rt, const int* p0, int max_ctx_now, const KvView& kv, float* scratch,
                            const Act& out, hipStream_t s) {
   const int n_local = n_real_per_seq + n_pseudo_per_seq;
   const int dh = kv.head_dim;
@@ -512,11 +514,11 @@ void launch_attention_mfma(const bf16* q_frag, int rows, int n_q_heads, int B, i
   float* part_ml = scratch + (size_t)rows * n_q_heads * FIRP_ATTN_MAX_SPLITS * dh;
   dim3 g(splits, kv.n_kv_heads, B), blk(64 * NWAVES);
   if (dh == 128)
-    hipLaunchKernelGGL(k_attention_mfma<128>, g, blk, 0, s, q_frag, n_q_heads, sr, n_local, rt.mask, p0, kv, chunk, part_o, part_ml, splits);
+    hipLaunchKernelGGL(k_attention_mfma<128>, g, blk, 0, s, q_frag, n_q_heads, sr, n_local, rt.mask, p0, seq0, kv, chunk, part_o, part_ml, splits);
   else if (dh == 64)
-    hipLaunchKernelGGL(k_attention_mfma<64>, g, blk, 0, s, q_frag, n_q_heads, sr, n_local, rt.mask, p0, kv, chunk, part_o, part_ml, splits);
+    hipLaunchKernelGGL(k_attention_mfma<64>, g, blk, 0, s, q_frag, n_q_heads, sr, n_local, rt.mask, p0, seq0, kv, chunk, part_o, part_ml, splits);
   else
-    hipLaunchKernelGGL(k_attention_mfma<32>, g, blk, 0, s, q_frag, n_q_heads, sr, n_local, rt.mask, p0, kv, chunk, part_o, part_ml, splits);
+    hipLaunchKernelGGL(k_attention_mfma<32>, g, blk, 0, s, q_frag, n_q_heads, sr, n_local, rt.mask, p0, seq0, kv, chunk, part_o, part_ml, splits);
   int hpb = std::max(1, 256 / (dh / 4));
   dim3 gc(rows, (n_q_heads + hpb - 1) / hpb), bc(dh / 4, hpb);
   hipLaunchKernelGGL(k_attn_combine<true>, gc, bc, 0, s, part_o, part_ml, splits, n_q_heads, dh, out);

@@ -94,7 +94,7 @@ struct firp_ctx {
   std::vector<int> p0, drafts_valid;
   HostTree cur;          // topology whose tables are on the device
   bool tables_valid = false;
-  int last_rows = 0, last_N = 0, last_P = 0;
+  int last_rows = 0, last_N = 0, last_P = 0, last_steps = 0;  // last_steps: pseudo rows per anchor
   // optional timing of the projection launches (HIP events on the library's stream)
   bool time_gemm = false;
   std::vector<hipEvent_t> ev;
@@ -344,7 +344,10 @@ void ensure_packed(firp_ctx* c) {
 // The decoder over B sequences of N real rows each; with n_anchor > 0 the pseudo rows of step i
 // (n_anchor per sequence) join at layer tl[i] (Eq. 3 on the residual stream entering it).  With
 // `head`, ends with final norm, lm-head and argmax / top-b.
-firp_status forward(firp_ctx* c, int B, int N, int n_anchor, bool head, int max_ctx_now) {
+// Only the maps [map_lo, map_hi) take part (all k of them in a decoding step, one in the
+// training forward); seq0 is the first sequence of the launch.
+firp_status forward(firp_ctx* c, int B, int N, int n_anchor, bool head, int max_ctx_now, int seq0, int map_lo,
+                    int map_hi) {
   if (c->gemm_kind == 1) ensure_packed(c);
   const firp_model_desc& d = c->d;
   hipStream_t s = c->stream;
@@ -352,7 +355,7 @@ firp_status forward(firp_ctx* c, int B, int N, int n_anchor, bool head, int max_
   const bool sp = c->split;
   const int qd = d.n_q_heads * d.head_dim, kvd = d.n_kv_heads * d.head_dim;
   const int real_rows = B * N, n_anchor_rows = B * n_anchor;
-  const int k_act = n_anchor > 0 ? c->k : 0;
+  const int k_act = n_anchor > 0 ? map_hi - map_lo : 0;
   launch_embed(c->embed, c->dtype, c->st.tok, real_rows, d.d_model, d.vocab, c->x, s);
   launch_rope_table(rt, c->st.p0, real_rows + k_act * n_anchor_rows, d.head_dim, d.rope_base, c->rope_tab, s);
   Partial pending{};  // projection output not yet added to the residual stream
@@ -364,7 +367,7 @@ firp_status forward(firp_ctx* c, int B, int N, int n_anchor, bool head, int max_
   for (int i = 0; i < c->k; ++i) pbias.b[i] = c->pb.empty() ? nullptr : c->pb[i];
   for (int layer = 0; layer <= d.n_layers; ++layer) {
     int m_new = m;
-    while (m_new < k_act && c->tl[m_new] == layer) ++m_new;
+    while (m_new < k_act && c->tl[map_lo + m_new] == layer) ++m_new;
     if (m_new > m) {
       // FIRP map (Eq. 3) of steps [m, m_new) on the raw residual stream of the anchor rows
       if (pending.p) launch_add_partial(c->x, pending, pending_rows, d.d_model, s);
@@ -373,14 +376,17 @@ firp_status forward(firp_ctx* c, int B, int N, int n_anchor, bool head, int max_
       const int nm = m_new - m;
       if (c->gemm_kind == 1 && c->packed && c->pk_proj_stacked && gemm_mfma_supported(n_anchor_rows, nm * d.d_model, d.d_model)) {
         // the maps share their input: one projection over the stacked copy, one scatter
-        Partial y = project(c, c->act_p, nullptr, c->pk_proj[m], n_anchor_rows, nm * d.d_model, d.d_model,
+        Partial y = project(c, c->act_p, nullptr, c->pk_proj[map_lo + m], n_anchor_rows, nm * d.d_model, d.d_model,
                             nm * d.d_model, 0, nullptr);
-        launch_scatter_pseudo(y, n_anchor_rows, d.d_model, c->k, m, nm, pbias, c->dtype, c->x, real_rows, s);
+        launch_scatter_pseudo(y, n_anchor_rows, d.d_model, c->k, map_lo + m, nm, pbias, c->dtype, c->x,
+                              real_rows + m * n_anchor_rows, s);
       } else {
-        for (int i = m; i < m_new; ++i) {
+        for (int j = m; j < m_new; ++j) {
+          const int i = map_lo + j;
           Partial y = project(c, c->act_p, c->pw[i], c->packed ? c->pk_proj[i] : nullptr, n_anchor_rows, d.d_model,
                               d.d_model, d.d_model, 0, nullptr);
-          launch_scatter_pseudo(y, n_anchor_rows, d.d_model, c->k, i, 1, pbias, c->dtype, c->x, real_rows, s);
+          launch_scatter_pseudo(y, n_anchor_rows, d.d_model, c->k, i, 1, pbias, c->dtype, c->x,
+                                real_rows + j * n_anchor_rows, s);
         }
       }
       m = m_new;
@@ -408,9 +414,10 @@ firp_status forward(firp_ctx* c, int B, int N, int n_anchor, bool head, int max_
                                 c->packed ? c->pk_qkv[layer] : nullptr, rows, d.d_model);
     KvView kv = kv_view(c, layer);
     if (c->attn_kind == 1 && sp) {
-      launch_rope_kv_tiles(q, rs, d.n_q_heads, B, N, n_local - N, n_anchor, c->st.p0, c->rope_tab, c->q_frag, kv, s);
-      launch_attention_mfma(c->q_frag, rows, d.n_q_heads, B, N, n_local - N, n_anchor, rt, c->st.p0, max_ctx_now, kv,
-                            c->attn_scratch, c->act_o, s);
+      launch_rope_kv_tiles(q, rs, d.n_q_heads, B, N, n_local - N, n_anchor, seq0, c->st.p0, c->rope_tab, c->q_frag, kv,
+                           s);
+      launch_attention_mfma(c->q_frag, rows, d.n_q_heads, B, N, n_local - N, n_anchor, seq0, rt, c->st.p0, max_ctx_now,
+                            kv, c->attn_scratch, c->act_o, s);
     } else {
       launch_rope_kv(q, rs, rows, d.n_q_heads, rt, c->st.p0, c->rope_tab, c->act_q, sp, kv, c->dtype, s);
       launch_attention_simple(c->act_q, sp, rows, d.n_q_heads, rt, c->st.p0, kv, c->dtype, c->act_o, n_local,
@@ -509,6 +516,16 @@ firp_status upload_tree(firp_ctx* c, int B, const std::vector<int>& parent, cons
   return FIRP_OK;
 }
 
+// masked keys are multiplied by a zero probability: the cache must never hold NaN or Inf
+firp_status ensure_cache_clean(firp_ctx* c) {
+  if (c->cache_clean) return FIRP_OK;
+  size_t bytes = (size_t)c->d.max_batch * c->kv_seq_stride * c->esize;
+  HIPCHK(hipMemsetAsync(c->kcache, 0, bytes, c->stream));
+  HIPCHK(hipMemsetAsync(c->vcache, 0, bytes, c->stream));
+  c->cache_clean = true;
+  return FIRP_OK;
+}
+
 firp_status check_tree(firp_ctx* c, const firp_tree* t, bool injected, std::vector<int>& parent,
                        std::vector<int>& rank, std::vector<uint8_t>& anchor, int& max_depth) {
   if (!t || !t->parent || (t->n_nodes > 1 && !t->rank)) return c->fail(FIRP_EINVAL, "tree or its arrays are NULL");
@@ -584,7 +601,7 @@ firp_status run_step(firp_ctx* c, const firp_tree* tree, const int32_t* node_tok
     inj = c->injected;
   }
   launch_fill_tokens(c->st, tree_tab(c, N, P), B, inj, s);
-  st = forward(c, B, N, n_anchor, true, ctx_max);
+  st = forward(c, B, N, n_anchor, true, ctx_max, 0, 0, c->k);
   if (st != FIRP_OK) return st;
   launch_verify_select(c->st, tree_tab(c, N, P), B, s);
   launch_kv_compact(kv_view(c, 0), c->kv_layer_stride, c->d.n_layers, B, c->st, c->dtype, s);
@@ -605,6 +622,7 @@ firp_status run_step(firp_ctx* c, const firp_tree* tree, const int32_t* node_tok
   c->last_rows = B * T;
   c->last_N = N;
   c->last_P = P;
+  c->last_steps = c->k;
   return FIRP_OK;
 }
 
@@ -712,6 +730,7 @@ firp_status firp_reset(firp_ctx* c) {
   if (!c) return FIRP_EINVAL;
   c->prefilled = false;
   c->batch = 0;
+  c->last_rows = 0;
   std::fill(c->p0.begin(), c->p0.end(), 0);
   std::fill(c->drafts_valid.begin(), c->drafts_valid.end(), 0);
   return FIRP_OK;
@@ -752,13 +771,8 @@ firp_status firp_prefill(firp_ctx* c, int32_t batch, const int32_t* tokens, cons
   hipStream_t s = c->stream;
   c->prefilled = false;
   c->tables_valid = false;
-  if (!c->cache_clean) {
-    // masked keys are multiplied by a zero probability: the cache must never hold NaN or Inf
-    size_t bytes = (size_t)c->d.max_batch * c->kv_seq_stride * c->esize;
-    HIPCHK(hipMemsetAsync(c->kcache, 0, bytes, s));
-    HIPCHK(hipMemsetAsync(c->vcache, 0, bytes, s));
-    c->cache_clean = true;
-  }
+  firp_status cst = ensure_cache_clean(c);
+  if (cst != FIRP_OK) return cst;
   // prompt[:-1] through the decoder in chunks: a chunk is a chain whose mask is lower-triangular
   std::vector<int> seq(C), local(C), pos(C);
   std::vector<unsigned long long> mask((size_t)C * FIRP_MASK_WORDS, 0);
@@ -780,7 +794,7 @@ firp_status firp_prefill(firp_ctx* c, int32_t batch, const int32_t* tokens, cons
     while (done < todo) {
       int n = std::min(C, todo - done);
       HIPCHK(hipMemcpyAsync(c->st.tok, tk + done, n * sizeof(int), hipMemcpyHostToDevice, s));
-      firp_status st = forward(c, 1, n, 0, false, done);
+      firp_status st = forward(c, 1, n, 0, false, done, b, 0, 0);
       if (st != FIRP_OK) return st;
       launch_advance_by(c->st.p0, b, n, s);
       HIPCHK(hipStreamSynchronize(s));  // the token staging buffer is reused by the next chunk
@@ -803,6 +817,68 @@ firp_status firp_prefill(firp_ctx* c, int32_t batch, const int32_t* tokens, cons
     return st;
   }
   for (int b = 0; b < batch; ++b) first_token[b] = acc[(size_t)b * (FIRP_MAX_K + 1)];
+  return FIRP_OK;
+}
+
+firp_status firp_train_forward(firp_ctx* c, const int32_t* tokens, int32_t n, int32_t step, double* loss,
+                               float* kl) {
+  if (!c) return FIRP_EINVAL;
+  if (!tokens || !loss) return c->fail(FIRP_EINVAL, "argument pointer is NULL");
+  if (step < 1 || step > c->k) return c->fail(FIRP_EINVAL, "step %d outside [1, k = %d]", step, c->k);
+  if (n <= step) return c->fail(FIRP_EINVAL, "the sequence must be longer than the prediction step");
+  if (2 * n > c->d.max_rows) return c->fail(FIRP_ECAPACITY, "2n = %d rows exceed max_rows %d", 2 * n, c->d.max_rows);
+  if (c->prefilled) return c->fail(FIRP_ESTATE, "the training forward needs a context without sequences (firp_reset)");
+  for (int i = 0; i < n; ++i)
+    if (tokens[i] < 0 || tokens[i] >= c->d.vocab) return c->fail(FIRP_EINVAL, "token %d = %d outside the vocabulary", i, tokens[i]);
+  if (!(c->attn_kind == 1 && c->split) && (size_t)(c->d.head_dim + 2 * n) * sizeof(float) > 64 * 1024)
+    return c->fail(FIRP_ECAPACITY, "sequence exceeds the plain attention kernel's limit");
+  hipStream_t s = c->stream;
+  firp_status st = ensure_cache_clean(c);
+  if (st != FIRP_OK) return st;
+  // rows [h_1..h_n, h~_1..h~_n] of sequence 0 on an empty cache: the real rows are a chain; pseudo
+  // row j (0-based) stands for position j + step, sees real rows 0 .. j + step - 1 and itself
+  const int R = 2 * n;
+  std::vector<int> seq(R, 0), local(R), pos(R), psrc(n);
+  std::vector<unsigned long long> mask((size_t)R * FIRP_MASK_WORDS, 0);
+  auto set = [&](int r, int bit) { mask[(size_t)r * FIRP_MASK_WORDS + (bit >> 6)] |= 1ull << (bit & 63); };
+  for (int v = 0; v < n; ++v) {
+    local[v] = pos[v] = v;
+    for (int i = 0; i <= v; ++i) set(v, i);
+    const int r = n + v;
+    local[r] = r;
+    pos[r] = v + step;
+    for (int i = 0; i < std::min(v + step, n); ++i) set(r, i);
+    set(r, r);
+    psrc[v] = v;
+  }
+  c->tables_valid = false;
+  HIPCHK(hipStreamSynchronize(s));
+  HIPCHK(hipMemcpy(c->rt_seq, seq.data(), R * sizeof(int), hipMemcpyHostToDevice));
+  HIPCHK(hipMemcpy(c->rt_local, local.data(), R * sizeof(int), hipMemcpyHostToDevice));
+  HIPCHK(hipMemcpy(c->rt_pos, pos.data(), R * sizeof(int), hipMemcpyHostToDevice));
+  HIPCHK(hipMemcpy(c->rt_mask, mask.data(), mask.size() * sizeof(unsigned long long), hipMemcpyHostToDevice));
+  HIPCHK(hipMemcpy(c->pseudo_src, psrc.data(), n * sizeof(int), hipMemcpyHostToDevice));
+  HIPCHK(hipMemcpy(c->st.tok, tokens, n * sizeof(int), hipMemcpyHostToDevice));
+  launch_set_root(c->st, 0, tokens[0], 0, s);   // cache length 0
+  st = forward(c, 1, n, n, true, 0, 0, step - 1, step);
+  if (st != FIRP_OK) return st;
+  float* d_kl = (float*)c->attn_scratch;   // free again once the last attention has run
+  launch_kl_rows(c->logits, c->d.vocab, n, step, d_kl, s);
+  std::vector<float> h_kl(n - step);
+  HIPCHK(hipMemcpyAsync(h_kl.data(), d_kl, (size_t)(n - step) * sizeof(float), hipMemcpyDeviceToHost, s));
+  HIPCHK(hipStreamSynchronize(s));
+  c->ev_used = 0;
+  double total = 0.0;
+  for (int q = 0; q < n - step; ++q) {
+    total += (double)h_kl[q];
+    if (kl) kl[q] = h_kl[q];
+  }
+  *loss = total;
+  c->batch = 1;          // for the logits read-out; the context still holds no sequence
+  c->last_rows = R;
+  c->last_N = n;
+  c->last_P = n;
+  c->last_steps = 1;
   return FIRP_OK;
 }
 
@@ -837,14 +913,14 @@ firp_status firp_check_tree(firp_ctx* c, const firp_tree* tree, int32_t* n_rows)
 firp_status firp_debug_last_logits(firp_ctx* c, float* logits, int32_t* n_rows) {
   if (!c) return FIRP_EINVAL;
   if (!logits || !n_rows) return c->fail(FIRP_EINVAL, "argument pointer is NULL");
-  if (!c->prefilled || c->last_rows == 0) return c->fail(FIRP_ESTATE, "no step has run");
+  if (c->last_rows == 0) return c->fail(FIRP_ESTATE, "no step has run");
   int B = c->batch, N = c->last_N, P = c->last_P, T = N + P, V = c->d.vocab;
   HIPCHK(hipStreamSynchronize(c->stream));
   for (int b = 0; b < B; ++b) {
     HIPCHK(hipMemcpy(logits + ((size_t)b * T) * V, c->logits + ((size_t)b * N) * V, (size_t)N * V * sizeof(float), hipMemcpyDeviceToHost));
     // pseudo rows: step by step, inside a step sequence by sequence; handed out per sequence
-    const int A = c->k > 0 ? P / c->k : 0;
-    for (int i = 0; i < c->k && A > 0; ++i)
+    const int A = c->last_steps > 0 ? P / c->last_steps : 0;
+    for (int i = 0; i < c->last_steps && A > 0; ++i)
       HIPCHK(hipMemcpy(logits + ((size_t)b * T + N + (size_t)i * A) * V,
                        c->logits + ((size_t)B * N + (size_t)i * B * A + (size_t)b * A) * V, (size_t)A * V * sizeof(float),
                        hipMemcpyDeviceToHost));

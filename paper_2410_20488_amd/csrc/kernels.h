@@ -69,8 +69,8 @@ void launch_swiglu(const Partial& gate_up, const RowScale& rs, int rows, int d_f
 void launch_gather_rows(const float* x, const int* src_rows, int rows, int d, const Act& out,
                         bool split, hipStream_t s);
 // ... and scatter the maps' outputs (+ bias) to the pseudo rows: y holds `k_in_y` maps side by
-// side starting with map i0; anchor row g of map i goes to row first_pseudo_row +
-// i * n_anchor_rows + g (pseudo rows are ordered step by step).
+// side starting with map i0; anchor row g of the j-th of them goes to row first_pseudo_row +
+// j * n_anchor_rows + g (pseudo rows are ordered step by step).
 struct PseudoBias {
   const void* b[8];  // per map, nullptr = none
 };
@@ -81,6 +81,8 @@ void launch_scatter_pseudo(const Partial& y, int n_anchor_rows, int d, int k, in
 size_t argmax_scratch_bytes(int rows, int b_max);
 void launch_argmax_topb(const Partial& logits, const RowScale& rs, float* logits_out, int real_rows, int rows,
                         int vocab, int b_max, int* amax, int* top, void* scratch, hipStream_t s);
+// Training stage, Eq. 4: kl[q] = KL(softmax(logits[n+q]) , softmax(logits[q+step])), q < n - step
+void launch_kl_rows(const float* logits, int vocab, int n, int step, float* kl, hipStream_t s);
 void launch_verify_select(const SeqState& st, const TreeTab& tt, int B, hipStream_t s);
 // move the accepted path's K/V to the front of the step's slots; advances nothing.
 void launch_kv_compact(const KvView& kv_layer0, size_t layer_stride, int n_layers, int B,
@@ -99,13 +101,14 @@ void launch_attention_simple(const Act& q, bool split, int rows, int n_q_heads, 
 bool attention_mfma_supported(int head_dim, int dtype);
 size_t attention_mfma_scratch_floats(int rows, int n_q_heads, int head_dim);
 void launch_attention_mfma(const bf16* q_frag, int rows, int n_q_heads, int B, int n_real_per_seq,
-                           int n_pseudo_per_seq, int n_anchor_per_seq, const RowTab& rt, const int* p0, int max_ctx_now,
+                           int n_pseudo_per_seq, int n_anchor_per_seq, int seq0, const RowTab& rt, const int* p0, int max_ctx_now,
                            const KvView& kv, float* scratch, const Act& out, hipStream_t s);
+// (seq0: first sequence of the launch; a prefill chunk runs one sequence as a batch of one.)
 // Its operand producer (replaces launch_rope_kv on this path): q as MFMA fragments in q_frag
 // (attention_q_frag_elems bf16 elements), K and V^T into the cache.
 size_t attention_q_frag_elems(int rows, int max_batch, int n_q_heads, int head_dim);
 void launch_rope_kv_tiles(const Partial& qkv, const RowScale& rs, int n_q_heads, int B, int n_real_per_seq,
-                          int n_pseudo_per_seq, int n_anchor_per_seq, const int* p0, const float2* tab, bf16* q_frag, const KvView& kv,
+                          int n_pseudo_per_seq, int n_anchor_per_seq, int seq0, const int* p0, const float2* tab, bf16* q_frag, const KvView& kv,
                           hipStream_t s);
 
 // plain tiled projection: y[S=1][rows][n] = x_f32[rows][K] . W[n][K]^T

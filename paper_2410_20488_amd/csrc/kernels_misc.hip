@@ -251,8 +251,9 @@ void launch_gather_rows(const float* x, const int* src_rows, int rows, int d, co
 template <typename BT>
 __global__ void k_scatter_pseudo(Partial y, int d, int k, int i0, int k_in_y, PseudoBias bias, float* x,
                                  int first_pseudo_row) {
+  // map i0 + blockIdx.y; its rows start at first_pseudo_row + blockIdx.y * (anchor rows)
   const int g = blockIdx.x, i = i0 + blockIdx.y;
-  float* xr = x + (size_t)(first_pseudo_row + i * (int)gridDim.x + g) * d;
+  float* xr = x + (size_t)(first_pseudo_row + (int)blockIdx.y * (int)gridDim.x + g) * d;
   const BT* bi = (const BT*)bias.b[i];
   const int c = blockIdx.z * blockDim.x + threadIdx.x;
   if (c >= d) return;
@@ -396,6 +397,52 @@ void launch_argmax_topb(const Partial& logits, const RowScale& rs, float* logits
     hipLaunchKernelGGL(k_argmax_part<16>, g, dim3(256), 0, s, logits, rs, logits_out, real_rows, vocab, b_max, cand);
     hipLaunchKernelGGL(k_argmax_merge<16>, dim3(rows), dim3(64), 0, s, cand, real_rows, vocab, b_max, amax, top);
   }
+}
+
+// ------------------------------------------------------------------------------------------
+// Training stage, Eq. 4: kl[q] = KL(softmax(logits[n + q]), softmax(logits[q + step])) for
+// q < n - step, with KL(A, B) = sum_t A_t (log A_t - log B_t).  One block per q; three passes
+// over the two rows (maxima, normalisers, the sum).
+__global__ __launch_bounds__(256) void k_kl_rows(const float* __restrict__ logits, int vocab, int n, int step,
+                                                 float* __restrict__ kl) {
+  __shared__ float red[4];
+  const int q = blockIdx.x;
+  const float* a = logits + (size_t)(n + q) * vocab;
+  const float* b = logits + (size_t)(q + step) * vocab;
+  float ma = -__builtin_inff(), mb = -__builtin_inff();
+  for (int t = threadIdx.x; t < vocab; t += 256) {
+    ma = fmaxf(ma, a[t]);
+    mb = fmaxf(mb, b[t]);
+  }
+  ma = wave_max(ma);
+  mb = wave_max(mb);
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = ma;
+  __syncthreads();
+  ma = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = mb;
+  __syncthreads();
+  mb = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+  float sa = 0.f, sb = 0.f;
+  for (int t = threadIdx.x; t < vocab; t += 256) {
+    sa += expf(a[t] - ma);
+    sb += expf(b[t] - mb);
+  }
+  sa = block_sum_256(sa, red);
+  sb = block_sum_256(sb, red);
+  const float la = ma + logf(sa), lb = mb + logf(sb);   // log normalisers
+  float acc = 0.f;
+  for (int t = threadIdx.x; t < vocab; t += 256) {
+    const float lpa = a[t] - la;
+    acc += expf(lpa) * (lpa - (b[t] - lb));
+  }
+  acc = block_sum_256(acc, red);
+  if (threadIdx.x == 0) kl[q] = acc;
+}
+
+void launch_kl_rows(const float* logits, int vocab, int n, int step, float* kl, hipStream_t s) {
+  hipLaunchKernelGGL(k_kl_rows, dim3(n - step), dim3(256), 0, s, logits, vocab, n, step, kl);
 }
 
 // ------------------------------------------------------------------------------------------

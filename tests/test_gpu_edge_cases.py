@@ -14,11 +14,13 @@ pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
 
 
-def test_two_sequences_with_different_prompts(progress):
+@pytest.mark.parametrize("name,tol", [("tiny", 1e-4), ("tiny_bf16", 2e-2)])
+def test_two_sequences_with_different_prompts(progress, name, tol):
     """Independent sequences share weights and topology, have their own cache length, drafts and
     path; a sequence without drafts rides along with 'no candidate' tokens and must return what
-    its own root-only step returns."""
-    cfg = synth.CONFIGS["tiny"]
+    its own root-only step returns.  (bf16: the MFMA kernels, whose prefill runs every sequence
+    as a batch of one at its own cache offset.)"""
+    cfg = synth.CONFIGS[name]
     w = synth.make_weights(cfg, DEV, with_bias=True)
     tree = synth.full_tree((3, 2), "root")
     N, k = tree.n_nodes, cfg.k
@@ -58,7 +60,7 @@ def test_two_sequences_with_different_prompts(progress):
             ref = r.logits.double().numpy()
             rows = [0] + list(range(N, N + k)) if r.ran_root_only else list(range(N + k))
             err = np.abs(lg[b][rows].astype(np.float64) - ref).max() / ref.std()
-            assert err < 1e-4, (step, b, err)
+            assert err < tol, (step, b, err)
             if not r.ran_root_only:
                 assert paths[b] == r.path
             assert bool(valid[b]) == (r.drafts is not None)
