@@ -7,17 +7,20 @@ bool gemm_mfma_supported(int rows, int n, int K) {
   return rows >= 1 && n >= 4 && n % 4 == 0 && K >= 8 && K % 8 == 0;
 }
 
-static int pick_nt(int rows) {
-  int nt = (std::min(rows, 128) + 15) / 16;
-  const int nts[] = {1, 2, 3, 4, 5, 6, 8};
+// activation tiles of one pass: up to 8 (128 rows), or up to 16 (256 rows) for 4-wave workgroups
+static int pick_nt(int rows, int nw) {
+  const int cap = nw == 4 ? 256 : 128;
+  int nt = (std::min(rows, cap) + 15) / 16;
+  const int nts[] = {1, 2, 3, 4, 5, 6, 8, 10, 12, 16};
   for (int c : nts)
     if (c >= nt) return c;
-  return 8;
+  return 16;
 }
+
 
 GemmPlan gemm_mfma_plan_ex(int rows, int n, int K, int S, int nw) {
   GemmPlan p{};
-  p.nt = pick_nt(rows);
+  p.nt = pick_nt(rows, nw);
   p.nw = nw;
   int tiles = (n + nw * 32 - 1) / (nw * 32);
   int stages = (K + KC - 1) / KC;
@@ -38,13 +41,17 @@ GemmPlan gemm_mfma_plan(int rows, int n, int K, int force_split) {
   const int n_cu = 256;
   int best_nw = 4, best_S = std::max(1, force_split);
   double best = -1.0;
-  for (int nw = 8; nw >= 2; --nw) {
+  // more than 128 rows: one pass over W per 256 rows with 4-wave workgroups (the instances with
+  // more than 8 activation tiles), instead of one pass per 128 rows
+  const int nw_hi = rows > 128 ? 4 : 8, nw_lo = rows > 128 ? 4 : 2;
+  if (rows > 128) best_nw = 4;
+  for (int nw = nw_hi; nw >= nw_lo; --nw) {
     int tiles = (n + nw * 32 - 1) / (nw * 32);
     int s_lo = force_split > 0 ? force_split : 1, s_hi = force_split > 0 ? force_split : 16;
     for (int S = s_lo; S <= s_hi; ++S) {
       if (force_split <= 0 && S > 1 && stages / S < 4) break;
       int grid = tiles * S;
-      if (grid > n_cu && !(nw == 2 && S == s_lo)) continue;
+      if (grid > n_cu && !(nw == nw_lo && S == s_lo)) continue;
       int per = (stages + S - 1) / S;
       // time ~ work of the busiest CU: rounds of the grid over the CUs times stages per workgroup
       double rounds = (double)((grid + n_cu - 1) / n_cu);
@@ -100,11 +107,12 @@ void launch_pack_weights(const WSeg& src, int n, int K, void* dst, hipStream_t s
 
 void launch_gemm_mfma(const Act& x, const void* w_packed, float* out, int ld, size_t part_stride, int rows, int n,
                       int K, const GemmPlan& plan, hipStream_t s) {
-  // more than 128 rows: row blocks of 128 (W is streamed once per block)
-  for (int r0 = 0; r0 < rows; r0 += 128) {
-    int rb = std::min(128, rows - r0);
+  // more rows than one pass takes: row blocks (W is streamed once per block)
+  const int block = plan.nw == 4 ? 256 : 128;
+  for (int r0 = 0; r0 < rows; r0 += block) {
+    int rb = std::min(block, rows - r0);
     GemmPlan p = plan;
-    p.nt = pick_nt(rb);
+    p.nt = pick_nt(rb, plan.nw);
     const bf16* xhi = x.hi + (size_t)r0 * x.ld;
     const bf16* xlo = x.lo + (size_t)r0 * x.ld;
     float* o = out + (size_t)r0 * ld;

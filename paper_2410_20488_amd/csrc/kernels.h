@@ -119,8 +119,8 @@ void launch_gemm_simple(const float* x, int ldx, const void* w, int dtype, float
 struct GemmPlan {
   int S;        // split-K factor
   int k_per;    // K elements per split (multiple of 64)
-  int nt;       // 16-row activation tiles
-  int nw;       // waves per workgroup (each owns 32 rows of W): 4, 8 or 16
+  int nt;       // 16-row activation tiles of one pass (up to 8; up to 16 with nw == 4)
+  int nw;       // waves per workgroup (each owns 32 rows of W): 2..8
   int grid;
 };
 #define FIRP_GEMM_NW 4
