@@ -14,9 +14,10 @@ def pytest_configure(config):
 
 
 def _progress(line: str) -> None:
-    """Tests report their own progress into gpurun_out/ so that a long, quiet GPU test is
+    """Tests report their own progress into a log file (directory: $FIRP_TEST_LOG_DIR, else the
+    scratch output folder at the repository root) so that a long, quiet GPU test is
     distinguishable from a hung one."""
-    d = os.path.join(ROOT, "gpurun_out")
+    d = os.environ.get("FIRP_TEST_LOG_DIR") or os.path.join(ROOT, "gpurun_out")
     try:
         os.makedirs(d, exist_ok=True)
         with open(os.path.join(d, "pytest_progress.log"), "a") as f:
