@@ -10,11 +10,16 @@ from tests.gpu_common import run_lockstep
 pytestmark = pytest.mark.gpu
 
 
-@pytest.mark.parametrize("name,prompt_len,n_steps", [("7b", 512, 4), ("13b", 1024, 3)])
-def test_full_depth_model_matches_oracle(name, prompt_len, n_steps, progress):
+@pytest.mark.parametrize("name,prompt_len,n_steps,layers", [("7b", 512, 4, None), ("13b", 1024, 3, None),
+                                                            ("7b", 256, 3, (15, 20, 25))])
+def test_full_depth_model_matches_oracle(name, prompt_len, n_steps, layers, progress):
+    """`layers`: one prediction layer per step (15/20/25 is the paper's setting for the 7B models)."""
     assert torch.cuda.is_available()
     dev = torch.device("cuda:0")
     cfg = synth.CONFIGS[name]
+    if layers is not None:
+        import dataclasses
+        cfg = dataclasses.replace(cfg, firp_layers=layers)
     progress(f"{name}: generating weights")
     w = synth.make_weights(cfg, dev)
     tree = synth.workload_tree(name)
