@@ -1,5 +1,6 @@
 """Edge cases of the step through the C ABI: several sequences, degenerate FIRP settings
-(k = 0, l = 0, l = L), every node an anchor with more than 128 rows, a long context."""
+(k = 0, l = 0, l = L), every node an anchor with more than 128 rows, a long context, the largest
+k and b, a one-token prompt, a context that fills up."""
 import dataclasses
 
 import numpy as np
@@ -113,3 +114,50 @@ def test_long_context_7b_widths(progress):
     rep, eng, orc = run_lockstep(cfg, w, tree, prompt_len=4100, n_steps=3, tol=2e-2, progress=progress)
     progress(f"long ctx: max logit err {rep.max_logit_err:.2e}")
     compare_cache(eng, orc, cfg)
+
+
+def test_maximum_steps_and_candidates(progress):
+    """The largest k and b the library takes: 8 prediction steps, top-16 candidates, a tree eight
+    levels deep (a chain plus branching near the root), with per-step layers on top."""
+    cfg = dataclasses.replace(synth.CONFIGS["tiny"], k=8, firp_layers=(0, 1, 1, 2, 2, 3, 3, 4))
+    w = synth.make_weights(cfg, DEV, with_bias=True)
+    paths = [()] + [tuple([0] * j) for j in range(1, 9)] + [(r,) for r in range(1, 16)] + [(15, 15), (3, 7, 9)]
+    paths += [(3, 7)]
+    paths = sorted(set(paths), key=lambda p: (len(p), p))
+    index = {p: i for i, p in enumerate(paths)}
+    parent = [-1] + [index[p[:-1]] for p in paths[1:]]
+    rank = [0] + [p[-1] for p in paths[1:]]
+    tree = synth.Tree(tuple(parent), tuple(rank), tuple([1] + [0] * (len(paths) - 1)))
+    rep, eng, orc = run_lockstep(cfg, w, tree, prompt_len=30, n_steps=8, tol=1e-4, progress=progress, b_max=16,
+                                 max_rows=64)
+    assert rep.tie_ambiguous == 0
+    assert max(i for i, c in enumerate(rep.accepted_hist) if c) >= 3
+    compare_cache(eng, orc, cfg)
+
+
+def test_one_token_prompt_and_full_context(progress):
+    """A prompt of one token (nothing to prefill, the root-only step runs on an empty cache), then
+    decoding until the context is full: the step that would not fit is refused with a capacity
+    error, nothing is enqueued, and the context stays usable after a reset."""
+    from paper_2410_20488_amd.binding import FirpError
+    cfg = synth.CONFIGS["tiny"]
+    w = synth.make_weights(cfg, DEV)
+    orc = make_oracle(cfg, cpu_weights(w))
+    eng = make_engine(cfg, w, max_ctx=12, max_nodes=4, max_rows=16)
+    tree = synth.chain_tree(3, "root")
+    args = dict(parent=list(tree.parent), rank=list(tree.rank), anchor=list(tree.anchor))
+    prompt = [17]
+    assert eng.prefill([prompt]) == [orc.prefill(prompt)]
+    assert eng.ctx_len() == [1] and orc.p0 == 1      # the root-only step committed the prompt's token
+    emitted = 0
+    with pytest.raises(FirpError) as e:
+        for _ in range(40):
+            want = orc.step(**args).tokens if orc.p0 + 4 <= 12 else None
+            got = eng.step(args["parent"], args["rank"], args["anchor"])[0]
+            assert want is not None and got == want
+            emitted += len(got)
+    assert "max_ctx" in str(e.value) and emitted >= 8
+    full = eng.ctx_len()[0]
+    assert full + 4 > 12                       # no room for a root plus three levels
+    eng.reset()
+    assert eng.prefill([prompt]) == [orc.fork().prefill(prompt)]
