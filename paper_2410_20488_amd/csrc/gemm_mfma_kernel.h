@@ -13,7 +13,7 @@
 //  * the activations are the small operand: a stage's [16*NT rows][64 k] tile of both planes
 //    (hi and lo bf16, see Act) is staged once per workgroup through LDS (double-buffered, row
 //    pitch 144 B so that 128-bit reads of 8 consecutive rows hit distinct banks) and shared by
-//    the four waves;
+//    the workgroup's waves;
 //  * fp32 accumulation in the MFMA accumulators; rows of X beyond `rows` and rows of W beyond
 //    `n` are read from clamped addresses and never stored;
 //  * K is cut into S contiguous splits so that (n / rows-per-workgroup) * S workgroups fill

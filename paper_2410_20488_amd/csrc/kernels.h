@@ -123,7 +123,6 @@ struct GemmPlan {
   int nw;       // waves per workgroup (each owns 32 rows of W): 2..8
   int grid;
 };
-#define FIRP_GEMM_NW 4
 GemmPlan gemm_mfma_plan_ex(int rows, int n, int K, int S, int nw);
 bool gemm_mfma_supported(int rows, int n, int K);
 GemmPlan gemm_mfma_plan(int rows, int n, int K, int force_split);  // force_split 0 = choose

@@ -273,7 +273,7 @@ void launch_scatter_pseudo(const Partial& y, int n_anchor_rows, int d, int k, in
 
 // ------------------------------------------------------------------------------------------
 // Greedy token of real rows, top-b of pseudo rows.  Order: larger logit first, ties to the
-// lower token id.  One block per row.
+// lower token id.
 struct Best {
   float v;
   int id;
