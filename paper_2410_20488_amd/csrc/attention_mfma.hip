@@ -148,10 +148,23 @@ __global__ __launch_bounds__(256) void k_rope_kv_tiles(Partial qkv, RowScale rs,
   __syncthreads();
   if (h >= n_q_heads + Hkv && h < heads) {
     const int hv = h - n_q_heads - Hkv;
-    unsigned short* vt = (unsigned short*)kv.v + (size_t)bs * kv.seq_stride + (size_t)hv * DH * kv.slots + p0 + tile * 16;
-    for (int idx = t; idx < DH * 16; idx += TPH) {
-      const int dim = idx >> 4, rr = idx & 15;
-      if (tile * 16 + rr < n_local) vt[(size_t)dim * kv.slots + rr] = vt_lds[hsel][rr][dim];
+    // slots p0 + 16 tile + rr of every dim: pairs of rows that start at an even slot go out as one
+    // 4-byte store (item j of a dim covers rows 2j - off and 2j - off + 1, off = parity of the
+    // tile's first slot)
+    const int sb = p0 + tile * 16, off = sb & 1;
+    unsigned short* vt = (unsigned short*)kv.v + (size_t)bs * kv.seq_stride + (size_t)hv * DH * kv.slots + sb;
+    for (int idx = t; idx < DH * 9; idx += TPH) {
+      const int dim = idx / 9, j = idx - dim * 9;
+      const int r0 = 2 * j - off, r1 = r0 + 1;
+      const bool ok0 = r0 >= 0 && r0 < 16 && tile * 16 + r0 < n_local;
+      const bool ok1 = r1 < 16 && tile * 16 + r1 < n_local;
+      unsigned short* dst = vt + (size_t)dim * kv.slots;
+      if (ok0 && ok1)
+        *(unsigned*)(dst + r0) = (unsigned)vt_lds[hsel][r0][dim] | ((unsigned)vt_lds[hsel][r1][dim] << 16);
+      else if (ok0)
+        dst[r0] = vt_lds[hsel][r0][dim];
+      else if (ok1)
+        dst[r1] = vt_lds[hsel][r1][dim];
     }
   }
 }
