@@ -25,9 +25,9 @@ HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E bandwidth
 GEMM_TRAFFIC_RATIO_13B = 1.116
 
 
-def algorithmic_bytes(cfg, n_nodes: int, t_hi: int, ctx: int) -> float:
-    """Bytes the method must move in one step: every weight once, the live KV cache once, the
-    step rows' K/V once out and once in (bf16 = 2 bytes)."""
+def algorithmic_bytes(cfg, n_nodes: int, t_hi: int, ctx: int, batch: int = 1) -> float:
+    """Bytes the method must move in one step: every weight once, and per sequence the live KV
+    cache once and the step rows' K/V once out and once in (bf16 = 2 bytes)."""
     e = 2 if cfg.dtype == "bf16" else 4
     kv_row = 2 * cfg.n_kv_heads * cfg.head_dim * e                 # K and V of one row, one layer
     weights = e * (cfg.n_layers * cfg.layer_params() + cfg.vocab * cfg.d_model + cfg.k * cfg.d_model ** 2)
@@ -35,7 +35,7 @@ def algorithmic_bytes(cfg, n_nodes: int, t_hi: int, ctx: int) -> float:
     n_anchor = (t_hi - n_nodes) // max(cfg.k, 1)
     step_rows = 2 * kv_row * sum(n_nodes + n_anchor * sum(1 for t in cfg.layers if t <= layer)
                                  for layer in range(cfg.n_layers))
-    return float(weights + kv_sweep + step_rows)
+    return float(weights + batch * (kv_sweep + step_rows))
 
 
 def cpu_baseline(cfg, weights_gpu, tree, prompt, budget_note: str):
@@ -83,9 +83,12 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=64)
     ap.add_argument("--warmup", type=int, default=8)
-    ap.add_argument("--config", default="13b", choices=["13b", "7b", "tiny_bf16"])
+    ap.add_argument("--config", default="13b", choices=["13b", "7b", "34b", "tiny_bf16"])
+    ap.add_argument("--batch", type=int, default=1, help="independent sequences decoded side by side")
     ap.add_argument("--prompt", type=int, default=0, help="prompt length (default: the configuration's)")
     ap.add_argument("--anchors", default="root", choices=["root", "all"])
+    ap.add_argument("--tree", default="", choices=["", "7b", "13b"],
+                    help="draft tree of another configuration (13b: the 64-node tree)")
     ap.add_argument("--firp-layers", default="",
                     help="comma-separated prediction layer per step (e.g. 25,30,35: the paper's 13B setting); "
                          "default: the benchmark configuration's single layer")
@@ -120,8 +123,8 @@ def main() -> int:
         import dataclasses
         cfg = dataclasses.replace(cfg, firp_layers=tuple(int(t) for t in args.firp_layers.split(",")))
         assert len(cfg.firp_layers) == cfg.k
-    tree = synth.workload_tree(args.config, args.anchors)
-    prompt_len = args.prompt or {"13b": 1024, "7b": 512, "tiny_bf16": 64}[args.config]
+    tree = synth.workload_tree(args.tree or args.config, args.anchors)
+    prompt_len = args.prompt or {"13b": 1024, "7b": 512, "34b": 2048, "tiny_bf16": 64}[args.config]
     t_start = time.time()
     weights = synth.make_weights(cfg, dev)
     torch.cuda.synchronize()
@@ -129,9 +132,10 @@ def main() -> int:
     t_hi = tree.n_nodes + cfg.k * n_anchor
     total_steps = args.warmup + args.steps + 16
     eng = make_engine(cfg, weights, max_ctx=prompt_len + (cfg.k + 1) * (total_steps + 2) + 8,
-                      max_nodes=tree.n_nodes, max_rows=max(128, t_hi), b_max=8)
-    prompt = synth.prompt_tokens(cfg.seed, prompt_len, cfg.vocab).tolist()
-    eng.prefill([prompt])
+                      max_batch=args.batch, max_nodes=tree.n_nodes, max_rows=max(128, t_hi), b_max=8)
+    prompts = [synth.prompt_tokens(cfg.seed, prompt_len, cfg.vocab, stream=b).tolist() for b in range(args.batch)]
+    prompt = prompts[0]
+    eng.prefill(prompts)
     setup_s = time.time() - t_start
     targs = (list(tree.parent), list(tree.rank), list(tree.anchor))
     for _ in range(args.warmup):
@@ -141,7 +145,7 @@ def main() -> int:
     t0 = time.perf_counter()
     tokens = 0
     for _ in range(args.steps):
-        tokens += len(eng.step(*targs)[0])
+        tokens += sum(len(t) for t in eng.step(*targs))
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ctx_last = eng.ctx_len()[0]
@@ -156,7 +160,7 @@ def main() -> int:
     eng.set_option("time_gemm", 0)
     gemm_gbs = gemm_bytes / (gemm_ms * 1e-3) / 1e9 if gemm_ms > 0 else 0.0
 
-    step_bytes = algorithmic_bytes(cfg, tree.n_nodes, t_hi, (ctx_first + ctx_last) // 2)
+    step_bytes = algorithmic_bytes(cfg, tree.n_nodes, t_hi, (ctx_first + ctx_last) // 2, args.batch)
     step_gbs = step_bytes / (ms_per_step * 1e-3) / 1e9
     out = {
         "metric": "firp_step latency (ms) and achieved HBM GB/s vs peak, 13B-shape bf16, k=3",
@@ -164,7 +168,7 @@ def main() -> int:
         "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": False,
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"LLaMA-2-{args.config.upper()}-shaped decoder, bf16 random-init, k={cfg.k} maps at "
-                               f"layer {cfg.firp_layer if cfg.firp_layers is None else list(cfg.firp_layers)}, batch 1, prompt {prompt_len} uniform-random tokens, "
+                               f"layer {cfg.firp_layer if cfg.firp_layers is None else list(cfg.firp_layers)}, batch {args.batch}, prompt {prompt_len} uniform-random tokens, "
                                f"{tree.n_nodes}-node draft tree, anchors={args.anchors} (T_hi={t_hi}), "
                                f"ctx {ctx_first}->{ctx_last}"},
         "step_algorithmic_GB": round(step_bytes / 1e9, 3),
@@ -181,7 +185,7 @@ def main() -> int:
                      "algorithmic_MB_per_launch": round(gemm_bytes / max(launches, 1) / 1e6, 2),
                      "share_of_step_time": round(gemm_ms / 16 / ms_per_step, 3)},
     }
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and args.batch == 1:
         del eng
         out["cpu_baseline"] = cpu_baseline(cfg, weights, tree, prompt, "")
     print(json.dumps(out))

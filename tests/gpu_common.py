@@ -129,7 +129,12 @@ def run_lockstep(cfg, weights_gpu, tree: synth.Tree, *, prompt_len: int, n_steps
                 f"step {step}: token {got[j]} vs {r.tokens[j]} differ at margin {row[r.tokens[j]] - row[got[j]]:.3e} > {slack:.3e}"
             rep.tie_ambiguous += 1
             emitted += r.tokens
-            eng.prefill([prompt + emitted])            # re-base on the oracle's committed tokens
+            # re-base on the oracle's committed tokens (its cache holds all but the last of them)
+            t = eng.prefill([prompt + emitted[:-1]])[0]
+            if t != emitted[-1]:                       # the tie was on the bonus token: both continue from t
+                assert j == len(r.tokens) - 1 and t == got[j], f"step {step}: re-based first token {t}"
+                emitted[-1] = orc.root_token = t
+                orc.drafts = None
             resync = True
         else:
             emitted += r.tokens
@@ -153,6 +158,113 @@ def run_lockstep(cfg, weights_gpu, tree: synth.Tree, *, prompt_len: int, n_steps
         if progress:
             progress(f"step {step}: {len(r.tokens)} tokens, logit err {err:.2e}, ties so far {rep.tie_ambiguous}")
     return rep, eng, orc
+
+
+def run_lockstep_batch(cfg, weights_gpu, tree: synth.Tree, *, prompt_lens, n_steps: int, tol: float, b_max=8,
+                       max_rows=None, progress=None):
+    """Several sequences decoded side by side by one engine against one oracle per sequence.
+    Every step drives both sides with the same candidates, taken from the oracle's state (its
+    drafts, or its own greedy continuation planted along the last-child chain on alternating
+    steps), so that what the library drafted never feeds forward: its tokens, path, drafts and
+    all logits are compared after each step, with the same near-tie rule as `run_lockstep`."""
+    B, N, k = len(prompt_lens), tree.n_nodes, cfg.k
+    base = make_oracle(cfg, cpu_weights(weights_gpu), b_max=b_max)
+    orcs = [base] + [base.fork() for _ in range(B - 1)]
+    n_anchor = sum(tree.anchor)
+    eng = make_engine(cfg, weights_gpu, max_ctx=max(prompt_lens) + (k + 1) * (n_steps + 2) + 8, max_batch=B,
+                      max_nodes=N, max_rows=max_rows or (N + k * n_anchor), b_max=b_max)
+    prompts = [synth.prompt_tokens(cfg.seed + 31, n, cfg.vocab, stream=b).tolist() for b, n in enumerate(prompt_lens)]
+    first = eng.prefill(prompts)
+    assert first == [o.prefill(p) for o, p in zip(orcs, prompts)]
+    emitted = [[t] for t in first]
+    depth = [0] * N
+    for v in range(1, N):
+        depth[v] = depth[tree.parent[v]] + 1
+    args = dict(parent=list(tree.parent), rank=list(tree.rank), anchor=list(tree.anchor))
+    rep = LockstepReport(accepted_hist=[0] * (synth.FIRP_MAX_DEPTH + 2))
+    for step in range(n_steps):
+        cand = []
+        for b, o in enumerate(orcs):
+            if (step + b) % 2 == 0 and max(depth) > 0:
+                look = o.fork()
+                look.K, look.V, look.p0 = [t.clone() for t in o.K], [t.clone() for t in o.V], o.p0
+                look.root_token, look.drafts = o.root_token, None
+                truth = []
+                for _ in range(min(k, max(depth))):
+                    truth += look.step(parent=[-1], rank=[0], anchor=[0]).tokens
+                t = synth.prompt_tokens(step * 16 + b, N, cfg.vocab, stream=5).tolist()
+                t = [(x + 1) % cfg.vocab if x in truth else x for x in t]
+                t[0] = o.root_token
+                v = 0
+                for lvl in range((step // 2 + b) % (len(truth) + 1)):
+                    kids = [c for c in range(N) if tree.parent[c] == v]
+                    if not kids:
+                        break
+                    v = kids[-1]
+                    t[v] = truth[lvl]
+                cand.append(t)
+            elif o.drafts is not None:
+                cand.append(_tokens_from_drafts(tree, depth, o.drafts, o.root_token))
+            else:
+                cand.append(None)
+        # a sequence without candidates rides along with "no candidate" tokens: both sides then
+        # run its root-only step
+        res = [o.step(**args, node_tokens=c) if c is not None else o.step(**args) for o, c in zip(orcs, cand)]
+        got = eng.step_with_candidates(args["parent"], args["rank"], args["anchor"],
+                                       [c if c is not None else [0] + [-1] * (N - 1) for c in cand])
+        lg, paths = eng.last_logits(), eng.last_path()
+        d, valid = eng.drafts()
+        rebase = []
+        for b, r in enumerate(res):
+            ref = r.logits.to(torch.float64).numpy()
+            # the library's rows that the oracle's rows correspond to (a root-only step of the
+            # oracle has the root and, if the root is an anchor, its k pseudo rows)
+            rows = list(range(ref.shape[0]))
+            if r.ran_root_only:
+                rows = [0] + ([N + i * n_anchor for i in range(k)] if tree.anchor[0] else [])
+            assert len(rows) == ref.shape[0]
+            abs_err = float(np.abs(lg[b][rows].astype(np.float64) - ref).max())
+            err = abs_err / float(ref.std())
+            rep.max_logit_err = max(rep.max_logit_err, err)
+            assert err <= tol, f"step {step} sequence {b}: logit error {err:.3e} > {tol}"
+            slack = 2.0 * abs_err
+            path_g = paths[b] if not r.ran_root_only else r.path
+            emitted[b] += r.tokens
+            if got[b] != r.tokens or path_g != r.path:
+                j = next(i for i in range(min(len(got[b]), len(r.tokens)) + 1)
+                         if i >= len(got[b]) or i >= len(r.tokens) or got[b][i] != r.tokens[i])
+                assert j < len(got[b]) and j < len(r.tokens) and path_g[:j + 1] == r.path[:j + 1], \
+                    f"step {step} sequence {b}: walks differ structurally: {got[b]}/{path_g} vs {r.tokens}/{r.path}"
+                row = ref[r.path[j]]
+                assert row[got[b][j]] >= row[r.tokens[j]] - slack, f"step {step} sequence {b}: token beyond tolerance"
+                rep.tie_ambiguous += 1
+                rebase.append((b, j == len(r.tokens) - 1, got[b][j]))
+                continue
+            assert bool(valid[b]) == (r.drafts is not None), f"step {step} sequence {b}: drafts validity"
+            if r.drafts is not None and d[b].tolist() != r.drafts:
+                for i in range(k):
+                    row = ref[r.rows.pseudo_row(r.path[-1], i + 1)]
+                    g = d[b][i].tolist()
+                    assert len(set(g)) == len(g)
+                    for a, c in zip(g[:-1], g[1:]):
+                        assert row[a] >= row[c] - slack, f"step {step} sequence {b}: draft order beyond tolerance"
+                    assert row[g[-1]] >= np.delete(row, g).max() - slack, f"step {step} sequence {b}: draft set"
+                rep.tie_ambiguous += 1
+            rep.tokens += len(r.tokens)
+            rep.accepted_hist[len(r.tokens)] += 1
+        if rebase:   # a near-tie changed a committed token: restart every sequence from the oracle's text
+            t = eng.prefill([p + e[:-1] for p, e in zip(prompts, emitted)])
+            for b, o in enumerate(orcs):
+                if t[b] != emitted[b][-1]:             # the tie was on the bonus token: both continue from t
+                    assert (b, True, t[b]) in rebase, f"step {step} sequence {b}: re-based first token {t[b]}"
+                    emitted[b][-1] = o.root_token = t[b]
+                    o.drafts = None
+        assert eng.ctx_len() == [o.p0 for o in orcs], f"step {step}: context lengths"
+        rep.steps += 1
+        if progress:
+            progress(f"batch step {step}: {[len(r.tokens) for r in res]} tokens, max logit err "
+                     f"{rep.max_logit_err:.2e}, ties so far {rep.tie_ambiguous}")
+    return rep, eng, orcs
 
 
 def compare_cache(eng, orc, cfg, atol=1e-4):

@@ -29,3 +29,22 @@ def test_full_depth_model_matches_oracle(name, prompt_len, n_steps, layers, prog
              f"accepted histogram {rep.accepted_hist}")
     assert rep.steps == n_steps
     assert rep.tie_ambiguous <= n_steps        # near-ties are rare, not the rule
+
+
+def test_34b_widths_batch_of_four(progress):
+    """The launch configuration of the 34B-shaped workload (grouped-query attention with 64 query
+    and 8 key/value heads, width 8192, FFN 22016, four sequences x 67 rows = 268 rows in every
+    projection) at a depth the oracle finishes in seconds: 4 of the 48 layers, the maps at layer 2."""
+    from tests.gpu_common import run_lockstep_batch
+    dev = torch.device("cuda:0")
+    cfg = synth.scaled_config(synth.CONFIGS["34b"], 4, 2)
+    progress("34b widths: generating weights")
+    w = synth.make_weights(cfg, dev)
+    tree = synth.workload_tree("34b")
+    rep, eng, orcs = run_lockstep_batch(cfg, w, tree, prompt_lens=[96, 17, 64, 130], n_steps=4, tol=2e-2,
+                                        progress=progress)
+    progress(f"34b widths: max logit err {rep.max_logit_err:.3e}, ties {rep.tie_ambiguous}, "
+             f"accepted histogram {rep.accepted_hist}")
+    assert rep.steps == 4
+    assert rep.tie_ambiguous <= 8               # of 16 (sequence, step) pairs
+    assert sum(rep.accepted_hist[2:]) > 0        # planted continuations were accepted
