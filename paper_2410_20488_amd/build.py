@@ -9,7 +9,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libfirp.so")
-SOURCES = ["engine.hip", "kernels_misc.hip", "gemm_simple.hip", "gemm_mfma.hip", *[f"gemm_mfma_nw{i}.hip" for i in range(2, 9)], "attention_simple.hip", "attention_mfma.hip", "tree_search.hip"]
+SOURCES = ["engine.hip", "kernels_misc.hip", "gemm_simple.hip", "gemm_mfma.hip", "gemm_tall.hip", *[f"gemm_mfma_nw{i}.hip" for i in range(2, 9)], "attention_simple.hip", "attention_mfma.hip", "tree_search.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Xclang", "-target-feature", "-Xclang",
          "-packed-fp32-ops", "-Wno-unused-command-line-argument", "-Wno-pass-failed"]
 

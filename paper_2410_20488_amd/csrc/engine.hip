@@ -274,7 +274,7 @@ Partial project(firp_ctx* c, const Act& in, const void* w, const void* w_packed,
     if (timed) {
       (void)hipEventRecord(c->ev[c->ev_used++], c->stream);
       c->gemm_bytes += 2.0 * (double)n * (double)K;
-      c->gemm_launches += (rows + (plan.nw == 4 ? 255 : 127)) / (plan.nw == 4 ? 256 : 128);
+      c->gemm_launches += (rows + plan.row_block - 1) / plan.row_block;
     }
     out.S = plan.S;
   } else {
@@ -303,7 +303,7 @@ Partial project_stacked(firp_ctx* c, const Act& in, const void* w0, int n0, cons
     if (timed) {
       (void)hipEventRecord(c->ev[c->ev_used++], c->stream);
       c->gemm_bytes += 2.0 * (double)n * (double)K;
-      c->gemm_launches += (rows + (plan.nw == 4 ? 255 : 127)) / (plan.nw == 4 ? 256 : 128);
+      c->gemm_launches += (rows + plan.row_block - 1) / plan.row_block;
     }
     out.S = plan.S;
     return out;

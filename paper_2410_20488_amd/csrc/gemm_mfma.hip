@@ -3,24 +3,28 @@
 
 namespace firp {
 
+// the kernel for 129..256 rows (gemm_tall.hip); takes K % 64 == 0 only
+void launch_gemm_tall(const bf16* xhi, const bf16* xlo, int ldx, int rows, const void* w_packed, int n, int K,
+                      float* out, int ld, size_t part_stride, const GemmPlan& plan, hipStream_t s);
+static bool tall_shape(int rows, int K) { return rows > 128 && K % 64 == 0; }
+
 bool gemm_mfma_supported(int rows, int n, int K) {
   return rows >= 1 && n >= 4 && n % 4 == 0 && K >= 8 && K % 8 == 0;
 }
 
-// activation tiles of one pass: up to 8 (128 rows), or up to 16 (256 rows) for 4-wave workgroups
-static int pick_nt(int rows, int nw) {
-  const int cap = nw == 4 ? 256 : 128;
-  int nt = (std::min(rows, cap) + 15) / 16;
-  const int nts[] = {1, 2, 3, 4, 5, 6, 8, 10, 12, 16};
+// activation tiles of one pass of the streaming kernel: up to 8 (128 rows)
+static int pick_nt(int rows) {
+  int nt = (std::min(rows, 128) + 15) / 16;
+  const int nts[] = {1, 2, 3, 4, 5, 6, 8};
   for (int c : nts)
     if (c >= nt) return c;
-  return 16;
+  return 8;
 }
 
 
 GemmPlan gemm_mfma_plan_ex(int rows, int n, int K, int S, int nw) {
   GemmPlan p{};
-  p.nt = pick_nt(rows, nw);
+  p.nt = pick_nt(rows);
   p.nw = nw;
   int tiles = (n + nw * 32 - 1) / (nw * 32);
   int stages = (K + KC - 1) / KC;
@@ -29,6 +33,7 @@ GemmPlan gemm_mfma_plan_ex(int rows, int n, int K, int S, int nw) {
   p.S = S;  // splits past the end of K find no stage and leave zeros
   p.k_per = per * KC;
   p.grid = tiles * p.S;
+  p.row_block = (tall_shape(rows, K) && nw == 8) ? 256 : 128;
   return p;
 }
 
@@ -41,10 +46,10 @@ GemmPlan gemm_mfma_plan(int rows, int n, int K, int force_split) {
   const int n_cu = 256;
   int best_nw = 4, best_S = std::max(1, force_split);
   double best = -1.0;
-  // more than 128 rows: one pass over W per 256 rows with 4-wave workgroups (the instances with
-  // more than 8 activation tiles), instead of one pass per 128 rows
-  const int nw_hi = rows > 128 ? 4 : 8, nw_lo = rows > 128 ? 4 : 2;
-  if (rows > 128) best_nw = 4;
+  // more than 128 rows: the 8-wave kernel that takes 256 rows of W and up to 256 rows of X per
+  // workgroup (one pass over W per 256 rows); its split factor is chosen the same way
+  const int nw_hi = 8, nw_lo = tall_shape(rows, K) ? 8 : 2;
+  if (tall_shape(rows, K)) best_nw = 8;
   for (int nw = nw_hi; nw >= nw_lo; --nw) {
     int tiles = (n + nw * 32 - 1) / (nw * 32);
     int s_lo = force_split > 0 ? force_split : 1, s_hi = force_split > 0 ? force_split : 16;
@@ -108,15 +113,19 @@ void launch_pack_weights(const WSeg& src, int n, int K, void* dst, hipStream_t s
 void launch_gemm_mfma(const Act& x, const void* w_packed, float* out, int ld, size_t part_stride, int rows, int n,
                       int K, const GemmPlan& plan, hipStream_t s) {
   // more rows than one pass takes: row blocks (W is streamed once per block)
-  const int block = plan.nw == 4 ? 256 : 128;
+  const int block = plan.row_block;
   for (int r0 = 0; r0 < rows; r0 += block) {
     int rb = std::min(block, rows - r0);
     GemmPlan p = plan;
-    p.nt = pick_nt(rb, plan.nw);
+    p.nt = pick_nt(rb);
     const bf16* xhi = x.hi + (size_t)r0 * x.ld;
     const bf16* xlo = x.lo + (size_t)r0 * x.ld;
     float* o = out + (size_t)r0 * ld;
     const char* w = (const char*)w_packed;
+    if (rb > 128) {
+      launch_gemm_tall(xhi, xlo, x.ld, rb, w, n, K, o, ld, part_stride, p, s);
+      continue;
+    }
     switch (p.nw) {
       case 2: launch_gemm_mfma_nw<2>(xhi, xlo, x.ld, rb, w, n, K, o, ld, part_stride, p, s); break;
       case 3: launch_gemm_mfma_nw<3>(xhi, xlo, x.ld, rb, w, n, K, o, ld, part_stride, p, s); break;

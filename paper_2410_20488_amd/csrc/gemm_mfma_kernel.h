@@ -1,6 +1,6 @@
 // Kernel template of the weight-streaming skinny projection for bf16 weights on gfx950.
 //
-//   out[s][r][c] = sum_{k in split s} X[r][k] * W[c][k],   r < rows <= 128 (256 with 4 waves),  c < n
+//   out[s][r][c] = sum_{k in split s} X[r][k] * W[c][k],   r < rows <= 128,  c < n
 //
 // The step is bound by streaming W from HBM once, so the kernel is built around that stream:
 //  * every wave owns 16*MT rows of W and reads them straight from global memory into the
@@ -37,10 +37,8 @@ constexpr int PITCH = 144;   // bytes per LDS row: 128 data + 16 pad
 __device__ __forceinline__ bf16x8_t as_bf16x8(u32x4_t v) { return __builtin_bit_cast(bf16x8_t, v); }
 }  // namespace
 
-// More than 8 activation tiles (129..256 rows in one pass over W) need the whole register file
-// of a SIMD for one wave: those instances exist for 4-wave workgroups only.
 template <int NT, int MT, bool KTAIL, int NW>
-__global__ __launch_bounds__(64 * NW, (NT > 8 ? 1 : 2)) void k_gemm_mfma(const bf16* __restrict__ xhi, const bf16* __restrict__ xlo,
+__global__ __launch_bounds__(64 * NW, 2) void k_gemm_mfma(const bf16* __restrict__ xhi, const bf16* __restrict__ xlo,
                                                       int ldx, int rows, const char* __restrict__ wpk, int n, int K,
                                                       float* __restrict__ out, int ld_out, size_t part_stride,
                                                       int S, int k_per) {
@@ -112,16 +110,13 @@ __global__ __launch_bounds__(64 * NW, (NT > 8 ? 1 : 2)) void k_gemm_mfma(const b
   // flight.  The body is unrolled four times so that the rotation costs no register moves, and
   // every load is unconditional (stages past the end are clamped to the last one and ignored)
   // so that the compiler's wait counters stay exact.
-  // (above 8 activation tiles the X tile runs one stage ahead in a single register set: it comes
-  // from L2, and two sets of it would not fit the register file)
-  constexpr int XAHEAD = NT > 8 ? 1 : 2;
-  u32x4_t a0[MT][2], a1[MT][2], a2[MT][2], a3[MT][2], x0[XP], x1s[XAHEAD == 2 ? XP : 1];
-  u32x4_t (&x1)[XP] = *reinterpret_cast<u32x4_t (*)[XP]>(XAHEAD == 2 ? x1s : x0);
+  constexpr int XAHEAD = 2;
+  u32x4_t a0[MT][2], a1[MT][2], a2[MT][2], a3[MT][2], x0[XP], x1[XP];
   const int last = nstages - 1;
   if (nstages > 0) {
     load_x(x0, 0);
     load_w(a0, 0);
-    if constexpr (XAHEAD == 2) load_x(x1, min(1, last));
+    load_x(x1, min(1, last));
     load_w(a1, min(1, last));
     load_w(a2, min(2, last));
   }
@@ -135,28 +130,19 @@ __global__ __launch_bounds__(64 * NW, (NT > 8 ? 1 : 2)) void k_gemm_mfma(const b
     __syncthreads();
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
-      // activation fragments in groups of at most 8 tiles, 4 above 8 tiles (register budget)
-      constexpr int NG = NT <= 8 ? NT : 4;
+      bf16x8_t bh[NT], bl[NT];
 #pragma unroll
-      for (int nt0 = 0; nt0 < NT; nt0 += NG) {
-        bf16x8_t bh[NG], bl[NG];
+      for (int nt = 0; nt < NT; ++nt) {
+        const unsigned char* bp = buf + blds + nt * 16 * PITCH + j * 64;
+        bh[nt] = as_bf16x8(*(const u32x4_t*)bp);
+        bl[nt] = as_bf16x8(*(const u32x4_t*)(bp + PLANE));
+      }
 #pragma unroll
-        for (int g = 0; g < NG; ++g) {
-          if (nt0 + g < NT) {
-            const unsigned char* bp = buf + blds + (nt0 + g) * 16 * PITCH + j * 64;
-            bh[g] = as_bf16x8(*(const u32x4_t*)bp);
-            bl[g] = as_bf16x8(*(const u32x4_t*)(bp + PLANE));
-          }
-        }
+      for (int nt = 0; nt < NT; ++nt) {
 #pragma unroll
-        for (int g = 0; g < NG; ++g) {
-          if (nt0 + g < NT) {
-#pragma unroll
-            for (int mt = 0; mt < MT; ++mt) {
-              acc[mt][nt0 + g] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(cur[mt][j]), bh[g], acc[mt][nt0 + g], 0, 0, 0);
-              acc[mt][nt0 + g] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(cur[mt][j]), bl[g], acc[mt][nt0 + g], 0, 0, 0);
-            }
-          }
+        for (int mt = 0; mt < MT; ++mt) {
+          acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(cur[mt][j]), bh[nt], acc[mt][nt], 0, 0, 0);
+          acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(cur[mt][j]), bl[nt], acc[mt][nt], 0, 0, 0);
         }
       }
     }
@@ -215,13 +201,7 @@ void launch_gemm_mfma_nw(const bf16* xhi, const bf16* xlo, int ldx, int rows, co
       case 4: launch_nt_<4>(xhi, xlo, ldx, rows, w, n, K, out, ld, part_stride, p, s); break;                         \
       case 5: launch_nt_<5>(xhi, xlo, ldx, rows, w, n, K, out, ld, part_stride, p, s); break;                         \
       case 6: launch_nt_<6>(xhi, xlo, ldx, rows, w, n, K, out, ld, part_stride, p, s); break;                         \
-      default:                                                                                                        \
-        if constexpr (NW == 4) {                                                                                      \
-          if (p.nt > 12) { launch_nt_<16>(xhi, xlo, ldx, rows, w, n, K, out, ld, part_stride, p, s); break; }         \
-          if (p.nt > 10) { launch_nt_<12>(xhi, xlo, ldx, rows, w, n, K, out, ld, part_stride, p, s); break; }         \
-          if (p.nt > 8) { launch_nt_<10>(xhi, xlo, ldx, rows, w, n, K, out, ld, part_stride, p, s); break; }          \
-        }                                                                                                             \
-        launch_nt_<8>(xhi, xlo, ldx, rows, w, n, K, out, ld, part_stride, p, s); break;                               \
+      default: launch_nt_<8>(xhi, xlo, ldx, rows, w, n, K, out, ld, part_stride, p, s); break;                        \
     }                                                                                                                 \
   }
 

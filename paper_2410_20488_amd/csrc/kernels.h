@@ -119,9 +119,10 @@ void launch_gemm_simple(const float* x, int ldx, const void* w, int dtype, float
 struct GemmPlan {
   int S;        // split-K factor
   int k_per;    // K elements per split (multiple of 64)
-  int nt;       // 16-row activation tiles of one pass (up to 8; up to 16 with nw == 4)
+  int nt;       // 16-row activation tiles of one pass of the streaming kernel (up to 8)
   int nw;       // waves per workgroup (each owns 32 rows of W): 2..8
   int grid;
+  int row_block;  // activation rows one launch takes: 128, or 256 (the kernel for 129..256 rows)
 };
 GemmPlan gemm_mfma_plan_ex(int rows, int n, int K, int S, int nw);
 bool gemm_mfma_supported(int rows, int n, int K);

@@ -12,8 +12,10 @@ SHAPES = [  # rows, n, K
     (4, 5120, 5120), (16, 5120, 5120), (17, 4096, 4096), (41, 4096, 11008), (44, 11008, 4096),
     (64, 5120, 5120), (67, 5120, 5120), (67, 13824, 5120), (67, 5120, 13824), (67, 32000, 5120),
     (80, 1024, 8192), (128, 5120, 5120), (129, 1280, 5120), (200, 5120, 1024), (256, 2048, 5120),
-    # more than 128 rows: one pass per 256 rows (10, 12 and 16 activation tiles), ragged K, 256 + 12 rows
+    # more than 128 rows: one pass per 256 rows, ragged K, 256 + 12 rows
     (150, 5120, 5120), (190, 4096, 11008), (256, 13824, 5120), (160, 520, 352), (268, 5120, 5120),
+    # the 129..256-row kernel: n not a multiple of its 256-row tile or of 16, an odd number of stages, one stage
+    (192, 1000, 512), (255, 4100, 320), (130, 256, 64), (256, 260, 8192),
 ]
 
 
