@@ -61,6 +61,8 @@ __device__ __forceinline__ void wait_vmcnt() {
   __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | (7 << 4) | (15 << 8));
 }
 
+}  // namespace
+
 // XT: 16-row activation tiles per wave (even); the workgroup takes 32 * XT rows.
 template <int XT>
 __global__ __launch_bounds__(512, 2) void k_gemm_tall(const bf16* __restrict__ xhi, const bf16* __restrict__ xlo, int ldx,
@@ -198,6 +200,8 @@ __global__ __launch_bounds__(512, 2) void k_gemm_tall(const bf16* __restrict__ x
     }
   }
 }
+
+namespace {
 
 template <int XT>
 void launch_xt(const bf16* xhi, const bf16* xlo, int ldx, int rows, const char* w, int n, int K, float* out, int ld,
