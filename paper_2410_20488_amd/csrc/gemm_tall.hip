@@ -54,11 +54,12 @@ __device__ __forceinline__ unsigned lds_address(const void* p) {
   return (unsigned)(size_t)(const __attribute__((address_space(3))) unsigned char*)p;
 }
 
-// s_waitcnt with only the vector-memory counter set (gfx9 encoding: vmcnt in bits 3:0 and 15:14,
-// expcnt 6:4 and lgkmcnt 11:8 left at "do not wait")
+// Wait until at most N vector-memory loads of this wave are outstanding.  Inline assembly with a
+// memory clobber so that the compiler keeps the loads written before it before it: the count is
+// only right for the program order as written.
 template <int N>
 __device__ __forceinline__ void wait_vmcnt() {
-  __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | (7 << 4) | (15 << 8));
+  asm volatile("s_waitcnt vmcnt(%0)" : : "n"(N) : "memory");
 }
 
 }  // namespace
