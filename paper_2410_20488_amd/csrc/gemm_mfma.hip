@@ -37,34 +37,44 @@ GemmPlan gemm_mfma_plan_ex(int rows, int n, int K, int S, int nw) {
   return p;
 }
 
-// A CU streams at a capped rate however many workgroups it holds, so a launch is as fast as
-// its busiest CU: the plan puts at most one workgroup on each of the 256 CUs and makes them
-// as many as possible (tiles x splits <= 256), preferring fewer splits (less partial-sum
-// traffic) and then taller tiles (the activation tile is fetched once per workgroup).
+// A CU moves data at a capped rate however many workgroups it holds (its vector cache keeps only
+// so many lines in flight), so a launch is as fast as its busiest CU: the plan puts at most one
+// workgroup on each of the 256 CUs and picks waves per workgroup (nw: 32 rows of W each) and
+// split factor S by a model of that CU's time, in units of one 4 KiB stage of one wave's W:
+//   stages per workgroup x (nw + 0.6 x activation tiles)   W from HBM, the X tile (4 KiB per 16 rows
+//                                                          and stage) from L2 at 0.6 of that cost
+//   + rows x nw / 32                                       the partial sums it writes
+//   + 6 per stage short of 8                               a pipeline that never fills
+//   + S x rows x n / 2^18                                  the consumer kernel reading the partial sums
+// The constants come from launch times measured over (S, nw) at the LLaMA-2 7B and 13B shapes
+// (e.g. 5120 x 5120 at 67 rows: 8 x 5 waves; 4096 x 11008: 16 x 8).  Few waves with many
+// activation tiles are excluded: two waves cannot keep a CU's memory pipeline busy.
+static double plan_cost(int rows, int n, int K, int S, int nw, int nt) {
+  const int stages = (K + KC - 1) / KC;
+  const int per = (stages + S - 1) / S;
+  const int r = std::min(rows, 256);
+  return per * (nw + 0.6 * nt) + r * nw / 32.0 + 6.0 * std::max(0, 8 - per)
+         + (double)S * r * n / 262144.0;   // and the consumer reads every partial sum back (spread over 256 CUs)
+}
+
 GemmPlan gemm_mfma_plan(int rows, int n, int K, int force_split) {
   const int stages = (K + KC - 1) / KC;
   const int n_cu = 256;
-  int best_nw = 4, best_S = std::max(1, force_split);
+  const bool tall = tall_shape(rows, K);   // the 8-wave kernel for 129..256 rows per pass
+  const int nt = tall ? (std::min(rows, 256) + 15) / 16 : pick_nt(rows);
+  const int nw_hi = 8, nw_lo = tall ? 8 : std::min(4, std::max(2, nt));
+  int best_nw = nw_hi, best_S = std::max(1, force_split);
   double best = -1.0;
-  // more than 128 rows: the 8-wave kernel that takes 256 rows of W and up to 256 rows of X per
-  // workgroup (one pass over W per 256 rows); its split factor is chosen the same way
-  const int nw_hi = 8, nw_lo = tall_shape(rows, K) ? 8 : 2;
-  if (tall_shape(rows, K)) best_nw = 8;
   for (int nw = nw_hi; nw >= nw_lo; --nw) {
     int tiles = (n + nw * 32 - 1) / (nw * 32);
     int s_lo = force_split > 0 ? force_split : 1, s_hi = force_split > 0 ? force_split : 16;
     for (int S = s_lo; S <= s_hi; ++S) {
       if (force_split <= 0 && S > 1 && stages / S < 4) break;
       int grid = tiles * S;
-      if (grid > n_cu && !(nw == nw_lo && S == s_lo)) continue;
-      int per = (stages + S - 1) / S;
-      // time ~ work of the busiest CU: rounds of the grid over the CUs times stages per workgroup
-      double rounds = (double)((grid + n_cu - 1) / n_cu);
-      double cost = rounds * per * nw;                     // W bytes per CU in units of 32 rows x 1 stage
-      double ideal = (double)stages * ((n + 31) / 32) / n_cu;
-      double score = ideal / cost - 0.004 * S + 0.002 * nw;
-      if (score > best) {
-        best = score;
+      if (grid > n_cu && !(nw == nw_hi && S == s_lo)) continue;   // (the fallback: several rounds)
+      double cost = (double)((grid + n_cu - 1) / n_cu) * plan_cost(rows, n, K, S, nw, nt);
+      if (best < 0.0 || cost < best - 1e-9) {
+        best = cost;
         best_nw = nw;
         best_S = S;
       }
