@@ -33,7 +33,7 @@ GemmPlan gemm_mfma_plan_ex(int rows, int n, int K, int S, int nw) {
   p.S = S;  // splits past the end of K find no stage and leave zeros
   p.k_per = per * KC;
   p.grid = tiles * p.S;
-  p.row_block = (tall_shape(rows, K) && nw == 8) ? 256 : 128;
+  p.row_block = (tall_shape(rows, K) && (nw == 8 || nw == 6)) ? 256 : 128;
   return p;
 }
 
@@ -62,10 +62,11 @@ GemmPlan gemm_mfma_plan(int rows, int n, int K, int force_split) {
   const int n_cu = 256;
   const bool tall = tall_shape(rows, K);   // the 8-wave kernel for 129..256 rows per pass
   const int nt = tall ? (std::min(rows, 256) + 15) / 16 : pick_nt(rows);
-  const int nw_hi = 8, nw_lo = tall ? 8 : std::min(4, std::max(2, nt));
+  const int nw_hi = 8, nw_lo = tall ? 6 : std::min(4, std::max(2, nt));
   int best_nw = nw_hi, best_S = std::max(1, force_split);
   double best = -1.0;
   for (int nw = nw_hi; nw >= nw_lo; --nw) {
+    if (tall && nw == 7) continue;   // that kernel's workgroups own 256 or 192 rows of W
     int tiles = (n + nw * 32 - 1) / (nw * 32);
     int s_lo = force_split > 0 ? force_split : 1, s_hi = force_split > 0 ? force_split : 16;
     for (int S = s_lo; S <= s_hi; ++S) {

@@ -13,6 +13,8 @@
 //    accumulators (a quarter of a MiB) fit the register file with two waves per SIMD;
 //  * the waves form a 4 x 2 grid: wave (wg, xg) multiplies 64 rows of W by half of the X rows, so
 //    an activation fragment read from LDS feeds four MFMAs per plane instead of two;
+//    (MW = 3 instead of 4 tiles of W per wave makes the workgroup's tile 192 rows of W: for
+//    matrices whose 256-row tiles would leave a third of the CUs without work)
 //  * W goes through LDS too (each fragment is used by two waves): a thread stages two 16-byte
 //    pieces per 32-column half-stage in registers, three half-stages ahead; in LDS a fragment
 //    keeps its 1 KiB lane order, so the reads are linear;
@@ -64,8 +66,9 @@ __device__ __forceinline__ void wait_vmcnt() {
 
 }  // namespace
 
-// XT: 16-row activation tiles per wave (even); the workgroup takes 32 * XT rows.
-template <int XT>
+// XT: 16-row activation tiles per wave (even); the workgroup takes 32 * XT rows of X.
+// MW: 16-row tiles of W per wave (3 or 4); the workgroup takes 64 * MW rows of W.
+template <int XT, int MW>
 __global__ __launch_bounds__(512, 2) void k_gemm_tall(const bf16* __restrict__ xhi, const bf16* __restrict__ xlo, int ldx,
                                                       int rows, const char* __restrict__ wpk, int n, int K,
                                                       float* __restrict__ out, int ld_out, size_t part_stride, int S,
@@ -86,18 +89,22 @@ __global__ __launch_bounds__(512, 2) void k_gemm_tall(const bf16* __restrict__ x
   const int nh = 2 * nstages;   // 32-column half-stages
   const int r16 = lane & 15, kb = lane >> 4;
 
-  // W: the tile's 16 fragments of a half-stage; this thread stages fragments wave and wave + 8
-  // (wave-uniform bases, one per-lane offset)
+  // W: the tile's 4 MW fragments of a half-stage; this thread stages fragments wave and wave + 8
+  // (with 12 fragments the waves 4..7 repeat fragment 11: every wave issues the same two loads,
+  // and the repeated LDS writes store the same bytes).  Wave-uniform bases, one per-lane offset.
+  constexpr int NF = 4 * MW;
   const int kp32 = (K / 64) * 2;
   const int n16 = (n + 15) >> 4;
   const char* wsrc[2];
+  int wdst[2];
 #pragma unroll
   for (int i = 0; i < 2; ++i) {
-    const int t16 = min(tile * 16 + wave_u + 8 * i, n16 - 1);
+    const int f = min(wave_u + 8 * i, NF - 1);
+    const int t16 = min(tile * NF + f, n16 - 1);
     wsrc[i] = wpk + ((size_t)t16 * kp32 + (k_begin >> 5)) * 1024;
+    wdst[i] = f * 1024 + lane * 16;
   }
   const unsigned woff = lane * 16;
-  const int wdst = wave * 1024 + lane * 16;
   // X: a stage is 2 planes x XR/8 blocks of 8 rows x 128 B.  This wave moves blocks
   // wave + 8 j (j < XT/2) of both planes; its lane L fetches, for the row 8 (wave + 8 j) + L/8,
   // the piece (L % 8) ^ (L / 8): the same byte offset in both planes.
@@ -120,9 +127,9 @@ __global__ __launch_bounds__(512, 2) void k_gemm_tall(const bf16* __restrict__ x
       load_to_lds_16(xbase[i & 1] + (size_t)st * 128, xoff[i >> 1], l0 + (i & 1) * XPLANE + (i >> 1) * 8192);
   };
 
-  f32x4_t acc[4][XT];
+  f32x4_t acc[MW][XT];
 #pragma unroll
-  for (int mt = 0; mt < 4; ++mt)
+  for (int mt = 0; mt < MW; ++mt)
 #pragma unroll
     for (int xt = 0; xt < XT; ++xt) acc[mt][xt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 
@@ -142,7 +149,7 @@ __global__ __launch_bounds__(512, 2) void k_gemm_tall(const bf16* __restrict__ x
     dma_x(xb0, 0);
     load_w(w2, min(2, lasth));
   }
-  const int arow = (wg * 4) * 1024 + lane * 16;
+  const int arow = (wg * MW) * 1024 + lane * 16;
   // fragment reads: row 16 t + r16 is block 2 t + r16 / 8, line r16 % 8; piece (4 P + kb) ^ (r16 % 8)
   const int brow = xg * XT * 2048 + (r16 >> 3) * 1024 + (r16 & 7) * 128;
   const int bcol[2] = {((kb) ^ (r16 & 7)) * 16, ((4 + kb) ^ (r16 & 7)) * 16};
@@ -151,24 +158,24 @@ __global__ __launch_bounds__(512, 2) void k_gemm_tall(const bf16* __restrict__ x
     constexpr int P = decltype(parity)::value;
     unsigned char* wbuf = wb[P];
 #pragma unroll
-    for (int i = 0; i < 2; ++i) *(u32x4_t*)(wbuf + wdst + i * 8192) = cur[i];
+    for (int i = 0; i < 2; ++i) *(u32x4_t*)(wbuf + wdst[i]) = cur[i];
     if constexpr (P == 1) dma_x(xnext, min((hs >> 1) + 1, last));
     load_w(nxt, min(hs + 3, lasth));
     if constexpr (P == 0) wait_vmcnt<4>();
     lds_barrier();
-    bf16x8_t a[4];
+    bf16x8_t a[MW];
 #pragma unroll
-    for (int mt = 0; mt < 4; ++mt) a[mt] = as_bf16x8(*(const u32x4_t*)(wbuf + arow + mt * 1024));
+    for (int mt = 0; mt < MW; ++mt) a[mt] = as_bf16x8(*(const u32x4_t*)(wbuf + arow + mt * 1024));
 #pragma unroll
     for (int xt = 0; xt < XT; ++xt) {
       const unsigned char* bp = xcur + brow + bcol[P] + xt * 2048;
       const bf16x8_t bh = as_bf16x8(*(const u32x4_t*)bp);
       const bf16x8_t bl = as_bf16x8(*(const u32x4_t*)(bp + XPLANE));
 #pragma unroll
-      for (int mt = 0; mt < 4; ++mt)
+      for (int mt = 0; mt < MW; ++mt)
         acc[mt][xt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[mt], bh, acc[mt][xt], 0, 0, 0);
 #pragma unroll
-      for (int mt = 0; mt < 4; ++mt)
+      for (int mt = 0; mt < MW; ++mt)
         acc[mt][xt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[mt], bl, acc[mt][xt], 0, 0, 0);
     }
   };
@@ -191,8 +198,8 @@ __global__ __launch_bounds__(512, 2) void k_gemm_tall(const bf16* __restrict__ x
   // accumulator layout: lane holds C[w-row 4*(lane/16) + i][x-row lane%16], i = 0..3
   float* o = out + (size_t)split * part_stride;
 #pragma unroll
-  for (int mt = 0; mt < 4; ++mt) {
-    const int c = tile * 256 + wg * 64 + mt * 16 + 4 * kb;
+  for (int mt = 0; mt < MW; ++mt) {
+    const int c = (tile * NF + wg * MW + mt) * 16 + 4 * kb;
     if (c >= n) continue;
 #pragma unroll
     for (int xt = 0; xt < XT; ++xt) {
@@ -204,21 +211,27 @@ __global__ __launch_bounds__(512, 2) void k_gemm_tall(const bf16* __restrict__ x
 
 namespace {
 
-template <int XT>
+template <int XT, int MW>
 void launch_xt(const bf16* xhi, const bf16* xlo, int ldx, int rows, const char* w, int n, int K, float* out, int ld,
                size_t part_stride, const GemmPlan& p, hipStream_t s) {
   dim3 g(p.grid), b(512);
-  hipLaunchKernelGGL((k_gemm_tall<XT>), g, b, 0, s, xhi, xlo, ldx, rows, w, n, K, out, ld, part_stride, p.S, p.k_per);
+  hipLaunchKernelGGL((k_gemm_tall<XT, MW>), g, b, 0, s, xhi, xlo, ldx, rows, w, n, K, out, ld, part_stride, p.S, p.k_per);
 }
 
 }  // namespace
 
-// 129 <= rows <= 256, K % 64 == 0; plan.nw must be 8 (a workgroup owns 256 rows of W), plan.grid = tiles x S
+// 129 <= rows <= 256, K % 64 == 0; plan.nw is 8 or 6 (a workgroup owns 256 or 192 rows of W),
+// plan.grid = tiles x S
 void launch_gemm_tall(const bf16* xhi, const bf16* xlo, int ldx, int rows, const void* w_packed, int n, int K,
                       float* out, int ld, size_t part_stride, const GemmPlan& plan, hipStream_t s) {
   const char* w = (const char*)w_packed;
-  if (rows <= 192) launch_xt<6>(xhi, xlo, ldx, rows, w, n, K, out, ld, part_stride, plan, s);
-  else launch_xt<8>(xhi, xlo, ldx, rows, w, n, K, out, ld, part_stride, plan, s);
+  if (plan.nw == 6) {
+    if (rows <= 192) launch_xt<6, 3>(xhi, xlo, ldx, rows, w, n, K, out, ld, part_stride, plan, s);
+    else launch_xt<8, 3>(xhi, xlo, ldx, rows, w, n, K, out, ld, part_stride, plan, s);
+  } else {
+    if (rows <= 192) launch_xt<6, 4>(xhi, xlo, ldx, rows, w, n, K, out, ld, part_stride, plan, s);
+    else launch_xt<8, 4>(xhi, xlo, ldx, rows, w, n, K, out, ld, part_stride, plan, s);
+  }
 }
 
 }  // namespace firp

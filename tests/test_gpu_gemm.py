@@ -16,6 +16,8 @@ SHAPES = [  # rows, n, K
     (150, 5120, 5120), (190, 4096, 11008), (256, 13824, 5120), (160, 520, 352), (268, 5120, 5120),
     # the 129..256-row kernel: n not a multiple of its 256-row tile or of 16, an odd number of stages, one stage
     (192, 1000, 512), (255, 4100, 320), (130, 256, 64), (256, 260, 8192),
+    # shapes whose plan takes that kernel's 192-row tiles (the 34B-shaped gate|up matrix among them)
+    (256, 44032, 8192), (256, 1344, 1024), (180, 2112, 2048),
 ]
 
 
