@@ -243,6 +243,15 @@ firp_status firp_debug_gemm(const float *x, const void *w, float *y, int32_t row
                             int32_t k_dim, int32_t dtype, int32_t kind, void *workspace,
                             size_t workspace_bytes, void *hip_stream);
 
+/* Host only: the launch plan the library picks for a projection of `rows` activation rows with an
+ * [n, K] bf16 weight matrix (no device work; for tests of the planning logic).  Out (HOST, each may
+ * be NULL): split-K factor, K elements per split (a multiple of 64), waves per workgroup (each owns
+ * 32 rows of W), workgroups of one launch, and the activation rows one launch takes (128, or 256
+ * when the kernel for 129..256 rows applies).  FIRP_EINVAL for a shape the MFMA kernels do not take
+ * (rows < 1, n % 4 != 0, K % 8 != 0). */
+firp_status firp_debug_gemm_plan(int32_t rows, int32_t n, int32_t k_dim, int32_t *splits, int32_t *k_per_split,
+                                 int32_t *waves, int32_t *grid, int32_t *row_block);
+
 #ifdef __cplusplus
 }
 #endif

@@ -84,6 +84,7 @@ def load_library() -> C.CDLL:
         "firp_set_option": (C.c_int, [vp, C.c_char_p, C.c_int32]),
         "firp_get_gemm_timing": (C.c_int, [vp, C.POINTER(C.c_int64), C.POINTER(C.c_double), C.POINTER(C.c_double)]),
         "firp_gemm_workspace_bytes": (C.c_size_t, [C.c_int32, C.c_int32, C.c_int32]),
+        "firp_debug_gemm_plan": (C.c_int32, [C.c_int32, C.c_int32, C.c_int32] + [C.POINTER(C.c_int32)] * 5),
         "firp_debug_gemm": (C.c_int, [vp, vp, vp, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32, vp,
                                        C.c_size_t, vp]),
     }
@@ -97,7 +98,7 @@ def load_library() -> C.CDLL:
 EXPORTED = ["firp_workspace_bytes", "firp_init", "firp_init_layers", "firp_build_tree", "firp_train_forward", "firp_prefill", "firp_step", "firp_reset", "firp_destroy",
             "firp_last_error", "firp_step_with_candidates", "firp_check_tree", "firp_debug_last_logits", "firp_debug_last_path",
             "firp_get_drafts", "firp_get_ctx_len", "firp_debug_read_cache", "firp_set_option", "firp_get_gemm_timing",
-            "firp_gemm_workspace_bytes", "firp_debug_gemm"]
+            "firp_gemm_workspace_bytes", "firp_debug_gemm", "firp_debug_gemm_plan"]
 
 
 def _i32(a) -> np.ndarray:
@@ -318,3 +319,13 @@ def debug_gemm(x: torch.Tensor, w: torch.Tensor, kind: int) -> torch.Tensor:
     if rc != 0:
         raise FirpError(rc, "firp_debug_gemm")
     return y
+
+
+def gemm_plan(rows: int, n: int, k_dim: int) -> dict:
+    """The launch plan the library picks for a projection (host logic only, no GPU needed)."""
+    lib = load_library()
+    out = [C.c_int32() for _ in range(5)]
+    rc = lib.firp_debug_gemm_plan(rows, n, k_dim, *[C.byref(o) for o in out])
+    if rc != 0:
+        raise FirpError(rc, "firp_debug_gemm_plan")
+    return dict(zip(("splits", "k_per_split", "waves", "grid", "row_block"), (o.value for o in out)))

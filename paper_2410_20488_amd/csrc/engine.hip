@@ -1081,4 +1081,16 @@ firp_status firp_debug_gemm(const float* x, const void* w, float* y, int32_t row
   return hipGetLastError() == hipSuccess ? FIRP_OK : FIRP_EDEVICE;
 }
 
+firp_status firp_debug_gemm_plan(int32_t rows, int32_t n, int32_t k_dim, int32_t* splits, int32_t* k_per_split,
+                                 int32_t* waves, int32_t* grid, int32_t* row_block) {
+  if (!gemm_mfma_supported(rows, n, k_dim)) return FIRP_EINVAL;
+  const GemmPlan p = gemm_mfma_plan(rows, n, k_dim, 0);
+  if (splits) *splits = p.S;
+  if (k_per_split) *k_per_split = p.k_per;
+  if (waves) *waves = p.nw;
+  if (grid) *grid = p.grid;
+  if (row_block) *row_block = p.row_block;
+  return FIRP_OK;
+}
+
 }  // extern "C"
