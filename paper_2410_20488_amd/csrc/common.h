@@ -75,6 +75,14 @@ __device__ __forceinline__ void act_store4(const Act& a, size_t idx, float v0, f
   }
 }
 
+// ---- workgroup -> work item of a projection launch -------------------------------------------
+// Work item of a workgroup.  The hardware deals workgroups to the 8 XCDs (each with its own L2)
+// round-robin by id, and all workgroups of one split read the same columns of X: the items are
+// therefore numbered split by split and XCD x takes the contiguous items [x, x + 1) * grid / 8, so
+// that a split's slice of X is fetched into one or two L2s instead of all eight.  The launch is
+// padded to a multiple of 8 workgroups; the surplus ones (item >= tiles * S) leave at once.
+__device__ __forceinline__ int xcd_item(int block, int launched) { return (block & 7) * (launched >> 3) + (block >> 3); }
+
 // ---- split-K partial sums ------------------------------------------------------------------
 // A projection leaves S partial products [S][rows][n] (fp32); its consumer adds them up.
 struct Partial {

@@ -41,12 +41,14 @@ template <int NT, int MT, bool KTAIL, int NW>
 __global__ __launch_bounds__(64 * NW, 2) void k_gemm_mfma(const bf16* __restrict__ xhi, const bf16* __restrict__ xlo,
                                                       int ldx, int rows, const char* __restrict__ wpk, int n, int K,
                                                       float* __restrict__ out, int ld_out, size_t part_stride,
-                                                      int S, int k_per) {
+                                                      int S, int k_per, int tiles) {
   constexpr int XROWS = NT * 16;
   constexpr int PLANE = XROWS * PITCH;
   __shared__ __attribute__((aligned(16))) unsigned char lds[2][2 * PLANE];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int split = blockIdx.x % S, tile = blockIdx.x / S;
+  const int item = xcd_item(blockIdx.x, gridDim.x);
+  if (item >= tiles * S) return;
+  const int split = item / tiles, tile = item - split * tiles;
   const int n0 = tile * (NW * 16 * MT) + wave * (16 * MT);
   const int k_begin = split * k_per;
   const int k_end = min(K, k_begin + k_per);
@@ -179,20 +181,20 @@ template <int NW>
 void launch_gemm_mfma_nw(const bf16* xhi, const bf16* xlo, int ldx, int rows, const char* w, int n, int K, float* out,
                          int ld, size_t part_stride, const GemmPlan& p, hipStream_t s);
 
-#define FIRP_GEMM_INSTANTIATE(NW)                                                                                      \
+#define FIRP_GEMM_INSTANTIATE(NW)                                                                                     \
   template <int NT>                                                                                                   \
-  static void launch_nt_(const bf16* xhi, const bf16* xlo, int ldx, int rows, const char* w, int n, int K, float* out, \
+  static void launch_nt_(const bf16* xhi, const bf16* xlo, int ldx, int rows, const char* w, int n, int K, float* out,\
                          int ld, size_t part_stride, const GemmPlan& p, hipStream_t s) {                              \
-    dim3 g(p.grid), b(64 * NW);                                                                                       \
+    dim3 g((p.grid + 7) & ~7), b(64 * NW);                                                                            \
     if (K % KC)                                                                                                       \
       hipLaunchKernelGGL((k_gemm_mfma<NT, 2, true, NW>), g, b, 0, s, xhi, xlo, ldx, rows, w, n, K, out, ld,           \
-                         part_stride, p.S, p.k_per);                                                                  \
+                         part_stride, p.S, p.k_per, p.grid / p.S);                                                    \
     else                                                                                                              \
       hipLaunchKernelGGL((k_gemm_mfma<NT, 2, false, NW>), g, b, 0, s, xhi, xlo, ldx, rows, w, n, K, out, ld,          \
-                         part_stride, p.S, p.k_per);                                                                  \
+                         part_stride, p.S, p.k_per, p.grid / p.S);                                                    \
   }                                                                                                                   \
   template <>                                                                                                         \
-  void launch_gemm_mfma_nw<NW>(const bf16* xhi, const bf16* xlo, int ldx, int rows, const char* w, int n, int K,     \
+  void launch_gemm_mfma_nw<NW>(const bf16* xhi, const bf16* xlo, int ldx, int rows, const char* w, int n, int K,      \
                                float* out, int ld, size_t part_stride, const GemmPlan& p, hipStream_t s) {            \
     switch (p.nt) {                                                                                                   \
       case 1: launch_nt_<1>(xhi, xlo, ldx, rows, w, n, K, out, ld, part_stride, p, s); break;                         \

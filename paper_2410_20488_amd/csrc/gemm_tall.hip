@@ -72,7 +72,7 @@ template <int XT, int MW>
 __global__ __launch_bounds__(512, 2) void k_gemm_tall(const bf16* __restrict__ xhi, const bf16* __restrict__ xlo, int ldx,
                                                       int rows, const char* __restrict__ wpk, int n, int K,
                                                       float* __restrict__ out, int ld_out, size_t part_stride, int S,
-                                                      int k_per) {
+                                                      int k_per, int tiles) {
   constexpr int XR = 32 * XT;
   constexpr int XPLANE = XR * 128;   // one plane of a 64-column stage
   static_assert(XT % 2 == 0, "rows of the tile in units of 64");
@@ -82,7 +82,9 @@ __global__ __launch_bounds__(512, 2) void k_gemm_tall(const bf16* __restrict__ x
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wave_u = __builtin_amdgcn_readfirstlane(wave);
   const int wg = wave & 3, xg = wave >> 2;
-  const int split = blockIdx.x % S, tile = blockIdx.x / S;
+  const int item = xcd_item(blockIdx.x, gridDim.x);
+  if (item >= tiles * S) return;
+  const int split = item / tiles, tile = item - split * tiles;
   const int k_begin = split * k_per;
   const int k_end = min(K, k_begin + k_per);
   const int nstages = (k_end - k_begin) / 64;
@@ -214,8 +216,9 @@ namespace {
 template <int XT, int MW>
 void launch_xt(const bf16* xhi, const bf16* xlo, int ldx, int rows, const char* w, int n, int K, float* out, int ld,
                size_t part_stride, const GemmPlan& p, hipStream_t s) {
-  dim3 g(p.grid), b(512);
-  hipLaunchKernelGGL((k_gemm_tall<XT, MW>), g, b, 0, s, xhi, xlo, ldx, rows, w, n, K, out, ld, part_stride, p.S, p.k_per);
+  dim3 g((p.grid + 7) & ~7), b(512);
+  hipLaunchKernelGGL((k_gemm_tall<XT, MW>), g, b, 0, s, xhi, xlo, ldx, rows, w, n, K, out, ld, part_stride, p.S, p.k_per,
+                     p.grid / p.S);
 }
 
 }  // namespace
