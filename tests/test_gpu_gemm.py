@@ -45,3 +45,24 @@ def test_plain_projection_matches_fp64_matmul(rows, n, K, dtype):
     y = binding.debug_gemm(x, w, kind=0).cpu().double()
     ref = x.cpu().double() @ w.cpu().double().T
     assert float((y - ref).abs().max() / ref.std()) < 2e-5
+
+
+def _random_shapes(count, seed):
+    """Seeded shapes over everything the MFMA kernels take: any row count up to 300, n a multiple of
+    4, K a multiple of 8 (a quarter of them multiples of 64, which the kernel for 129..256 rows needs)."""
+    g = torch.Generator().manual_seed(seed)
+    out = []
+    for i in range(count):
+        rows = int(torch.randint(1, 301, (1,), generator=g))
+        n = 4 * int(torch.randint(1, 700, (1,), generator=g))
+        K = 64 * int(torch.randint(1, 40, (1,), generator=g)) if i % 4 else 8 * int(torch.randint(1, 300, (1,), generator=g))
+        out.append((rows, n, K))
+    return out
+
+
+@pytest.mark.parametrize("rows,n,K", _random_shapes(48, 20488))
+def test_mfma_projection_random_shapes(rows, n, K):
+    x, w = _inputs(rows, n, K, torch.bfloat16)
+    y = binding.debug_gemm(x, w, kind=1).cpu().double()
+    ref = x.cpu().double() @ w.cpu().double().T
+    assert float((y - ref).abs().max() / ref.std()) < 2e-4
