@@ -16,7 +16,8 @@ DEV = "cuda:0"
 
 @pytest.mark.parametrize("name,layers,n,tol_logit,tol_kl", [
     ("tiny", None, 23, 1e-4, 1e-4), ("tiny", (1, 2, 3), 40, 1e-4, 1e-4), ("tiny", (0, 2, 4), 17, 1e-4, 1e-4),
-    ("tiny_bf16", None, 64, 2e-2, 2e-3), ("tiny_bf16", (1, 2, 3), 37, 2e-2, 2e-3), ("tiny_gqa", None, 50, 2e-2, 2e-3)])
+    ("tiny_bf16", None, 64, 2e-2, 2e-3), ("tiny_bf16", (1, 2, 3), 37, 2e-2, 2e-3), ("tiny_gqa", None, 50, 2e-2, 2e-3),
+    ("tiny_bf16", None, 100, 2e-2, 2e-3), ("tiny_bf16", (0, 1, 3), 128, 2e-2, 2e-3)])   # 200 and 256 rows
 def test_train_forward_matches_oracle(name, layers, n, tol_logit, tol_kl, progress):
     """Every prediction step: all 2n rows of logits within the logit tolerance, every KL term
     within tol_kl of the largest term (the terms inherit the logits' error), the loss likewise."""
