@@ -48,3 +48,73 @@ def test_34b_widths_batch_of_four(progress):
     assert rep.steps == 4
     assert rep.tie_ambiguous <= 8               # of 16 (sequence, step) pairs
     assert sum(rep.accepted_hist[2:]) > 0        # planted continuations were accepted
+
+
+def test_13b_full_depth_decoding_is_lossless(progress):
+    """Eq. 1 at full size, with no oracle in the loop: what the step commits, with a 64-node tree,
+    pseudo rows and planted or self-drafted candidates, is token for token what plain greedy
+    decoding (a root-only tree, one row per step) produces from the same prompt; a planted
+    continuation of j tokens is accepted whole (j + 1 tokens committed) and nothing else is.
+    The two runs round differently (other launch shapes), so a token may differ where the two
+    best logits of its row are closer than the logit tolerance; such a near-tie is checked on the
+    logits, counted, and the plain run restarts from the text the step committed."""
+    from tests.gpu_common import make_engine
+    dev = torch.device("cuda:0")
+    cfg = synth.CONFIGS["13b"]
+    progress("13b lossless: generating weights")
+    w = synth.make_weights(cfg, dev)
+    prompt = synth.prompt_tokens(cfg.seed, 1024, cfg.vocab).tolist()
+    T = 48
+    plain = make_engine(cfg, w, max_ctx=1024 + T + 16, max_nodes=1, max_rows=8, b_max=8)
+
+    def greedy_text(known):
+        """`known` followed by what plain greedy decoding appends to prompt + known."""
+        g = list(known) + [plain.prefill([prompt + list(known)])[0]]
+        while len(g) < T + cfg.k + 2:
+            g += plain.step([-1], [0], [0])[0]
+        return g
+
+    g = greedy_text([])
+    progress(f"13b lossless: plain greedy decoding gave {len(g)} tokens")
+    tree = synth.workload_tree("13b")
+    N = tree.n_nodes
+    args = (list(tree.parent), list(tree.rank), list(tree.anchor))
+    eng = make_engine(cfg, w, max_ctx=1024 + T + 16, max_nodes=N, max_rows=128, b_max=8)
+    emitted = [eng.prefill([prompt])[0]]
+    assert emitted == g[:1]
+    step, ties, hist = 0, 0, [0] * (cfg.k + 2)
+    while len(emitted) < T:
+        pos = len(emitted)                      # g[pos] is the next token to come
+        plant = None
+        if step % 2 == 0:
+            # candidates that cannot match by accident, then the true continuation along the chain of last children
+            plant = (step // 2) % (cfg.k + 1)
+            cand = [(t + 7) % cfg.vocab if t in g[pos:pos + cfg.k + 1] else t
+                    for t in synth.prompt_tokens(step, N, cfg.vocab, stream=9).tolist()]
+            v = 0
+            for lvl in range(plant):
+                v = [c for c in range(N) if tree.parent[c] == v][-1]
+                cand[v] = g[pos + lvl]
+            got = eng.step_with_candidates(*args, [cand])[0]
+        else:
+            got = eng.step(*args)[0]            # its own drafts (untrained maps: whatever they are, the text may not change)
+        want = g[pos:pos + len(got)]
+        if got != want:
+            j = next(i for i in range(len(got)) if got[i] != want[i])
+            lg = eng.last_logits()[0]
+            row = lg[eng.last_path()[0][j]]     # the row whose greedy token is got[j]
+            gap = float(row[got[j]] - row[want[j]]) / float(lg.std())
+            assert 0.0 <= gap <= 2e-2, f"step {step}: token {got[j]} instead of {want[j]} at a logit gap of {gap:.2e} std"
+            ties += 1
+            emitted += got
+            g = greedy_text(emitted)
+            progress(f"13b lossless: near-tie at step {step} (gap {gap:.1e} std), plain run restarted")
+        else:
+            if plant is not None:
+                assert len(got) == plant + 1, (step, plant, got)
+            emitted += got
+        hist[len(got)] += 1
+        step += 1
+    assert eng.ctx_len()[0] == 1024 + len(emitted) - 1
+    progress(f"13b lossless: {len(emitted)} tokens in {step} steps, {ties} near-ties, tokens-per-step histogram {hist}")
+    assert hist[cfg.k + 1] > 0 and ties <= 3
