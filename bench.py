@@ -160,6 +160,10 @@ def main() -> int:
     eng.set_option("time_gemm", 0)
     gemm_gbs = gemm_bytes / (gemm_ms * 1e-3) / 1e9 if gemm_ms > 0 else 0.0
 
+    # the rate a kernel that only reads can reach on this chip (8 GiB, far beyond every cache)
+    from paper_2410_20488_amd import binding
+    ceiling_gbs = binding.stream_read_gbps()
+
     step_bytes = algorithmic_bytes(cfg, tree.n_nodes, t_hi, (ctx_first + ctx_last) // 2, args.batch)
     step_gbs = step_bytes / (ms_per_step * 1e-3) / 1e9
     out = {
@@ -174,6 +178,8 @@ def main() -> int:
         "step_algorithmic_GB": round(step_bytes / 1e9, 3),
         "step_achieved_GBps": round(step_gbs, 1),
         "step_frac_of_hbm_peak": round(step_gbs / HBM_PEAK_GBS, 4),
+        "stream_read_ceiling_GBps": round(ceiling_gbs, 1),
+        "step_frac_of_stream_read_ceiling": round(step_gbs / ceiling_gbs, 4),
         "tokens_per_step": round(tokens / args.steps, 3),
         "setup_s": round(setup_s, 1),
         "roofline": {"bound": "hbm", "kernel": "k_gemm_mfma", "achieved": round(gemm_gbs, 1), "peak": HBM_PEAK_GBS,

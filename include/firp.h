@@ -243,6 +243,12 @@ firp_status firp_debug_gemm(const float *x, const void *w, float *y, int32_t row
                             int32_t k_dim, int32_t dtype, int32_t kind, void *workspace,
                             size_t workspace_bytes, void *hip_stream);
 
+/* Measurement aid: one kernel that only reads `bytes` (>= 16, a multiple of 16 is read) of DEVICE
+ * memory at `src` (16-byte aligned) on `hip_stream`; `sink` is 4 bytes of DEVICE memory it may
+ * write.  Timing it over a buffer larger than every cache gives the streaming-read rate a kernel
+ * can reach on this chip, which bench.py reports beside the step's bandwidth. */
+firp_status firp_debug_stream_read(const void *src, size_t bytes, void *sink, void *hip_stream);
+
 /* Host only: the launch plan the library picks for a projection of `rows` activation rows with an
  * [n, K] bf16 weight matrix (no device work; for tests of the planning logic).  Out (HOST, each may
  * be NULL): split-K factor, K elements per split (a multiple of 64), waves per workgroup (each owns

@@ -84,6 +84,7 @@ def load_library() -> C.CDLL:
         "firp_set_option": (C.c_int, [vp, C.c_char_p, C.c_int32]),
         "firp_get_gemm_timing": (C.c_int, [vp, C.POINTER(C.c_int64), C.POINTER(C.c_double), C.POINTER(C.c_double)]),
         "firp_gemm_workspace_bytes": (C.c_size_t, [C.c_int32, C.c_int32, C.c_int32]),
+        "firp_debug_stream_read": (C.c_int32, [C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]),
         "firp_debug_gemm_plan": (C.c_int32, [C.c_int32, C.c_int32, C.c_int32] + [C.POINTER(C.c_int32)] * 5),
         "firp_debug_gemm": (C.c_int, [vp, vp, vp, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32, vp,
                                        C.c_size_t, vp]),
@@ -98,7 +99,7 @@ def load_library() -> C.CDLL:
 EXPORTED = ["firp_workspace_bytes", "firp_init", "firp_init_layers", "firp_build_tree", "firp_train_forward", "firp_prefill", "firp_step", "firp_reset", "firp_destroy",
             "firp_last_error", "firp_step_with_candidates", "firp_check_tree", "firp_debug_last_logits", "firp_debug_last_path",
             "firp_get_drafts", "firp_get_ctx_len", "firp_debug_read_cache", "firp_set_option", "firp_get_gemm_timing",
-            "firp_gemm_workspace_bytes", "firp_debug_gemm", "firp_debug_gemm_plan"]
+            "firp_gemm_workspace_bytes", "firp_debug_gemm", "firp_debug_gemm_plan", "firp_debug_stream_read"]
 
 
 def _i32(a) -> np.ndarray:
@@ -329,3 +330,22 @@ def gemm_plan(rows: int, n: int, k_dim: int) -> dict:
     if rc != 0:
         raise FirpError(rc, "firp_debug_gemm_plan")
     return dict(zip(("splits", "k_per_split", "waves", "grid", "row_block"), (o.value for o in out)))
+
+
+def stream_read_gbps(nbytes: int = 8 << 30, repeats: int = 5, device: str = "cuda:0") -> float:
+    """Rate of a plain streaming-read kernel over `nbytes` of device memory (GB/s, best of `repeats`)."""
+    lib = load_library()
+    buf = torch.zeros(nbytes, dtype=torch.uint8, device=device)
+    sink = torch.zeros(1, dtype=torch.int32, device=device)
+    stream = torch.cuda.current_stream(buf.device)
+    best = 0.0
+    for _ in range(repeats + 1):                      # the first pass warms up
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        rc = lib.firp_debug_stream_read(buf.data_ptr(), nbytes, sink.data_ptr(), stream.cuda_stream)
+        e1.record(stream)
+        if rc != 0:
+            raise FirpError(rc, "firp_debug_stream_read")
+        e1.synchronize()
+        best = max(best, nbytes / (e0.elapsed_time(e1) * 1e-3) / 1e9)
+    return best

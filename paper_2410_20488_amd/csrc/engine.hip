@@ -1081,6 +1081,12 @@ firp_status firp_debug_gemm(const float* x, const void* w, float* y, int32_t row
   return hipGetLastError() == hipSuccess ? FIRP_OK : FIRP_EDEVICE;
 }
 
+firp_status firp_debug_stream_read(const void* src, size_t bytes, void* sink, void* hip_stream) {
+  if (!src || !sink || bytes < 16 || (((uintptr_t)src) & 15)) return FIRP_EINVAL;
+  launch_stream_read(src, bytes, (unsigned*)sink, (hipStream_t)hip_stream);
+  return hipGetLastError() == hipSuccess ? FIRP_OK : FIRP_EDEVICE;
+}
+
 firp_status firp_debug_gemm_plan(int32_t rows, int32_t n, int32_t k_dim, int32_t* splits, int32_t* k_per_split,
                                  int32_t* waves, int32_t* grid, int32_t* row_block) {
   if (!gemm_mfma_supported(rows, n, k_dim)) return FIRP_EINVAL;

@@ -146,5 +146,6 @@ void launch_gemm_mfma(const Act& x, const void* w_packed, float* out, int ld, si
                       int n, int K, const GemmPlan& plan, hipStream_t s);
 void launch_split_act(const float* x, int rows, int ld, const Act& out, hipStream_t s);
 void launch_reduce_partials(const Partial& p, float* y, int rows, hipStream_t s);
+void launch_stream_read(const void* src, size_t bytes, unsigned* sink, hipStream_t s);
 
 }  // namespace firp
