@@ -29,8 +29,8 @@ What it computes (paper: Methodology / FIRP, Inference stage, Tree attention; Eq
 * the forward pass of the Training stage (Eq. 3-4): the 2n-row sequence of hidden and pseudo
   hidden states with its mask and position ids, and the KL loss (`train_forward`).
 
-Arithmetic is done in `dtype` (fp32 by default as the build's contract names an fp32 oracle;
-fp64 for the pins).  Weights are whatever bit patterns the caller hands over, widened
+Arithmetic is done in `dtype`: fp64 for the pins and the small-model parity tests, fp32 (the
+default) where the full-size models would take minutes in fp64.  Weights are whatever bit patterns the caller hands over, widened
 exactly.  K and V are optionally rounded to bf16 right after they are produced: that models
 a bf16 KV cache as a storage format (the only rounding besides `dtype` itself).
 

@@ -42,10 +42,11 @@ def _tokens_from_drafts(tree: synth.Tree, depth, drafts, root):
 
 
 def run_lockstep(cfg, weights_gpu, tree: synth.Tree, *, prompt_len: int, n_steps: int, tol: float,
-                 gemm=None, b_max=8, with_injection=True, max_rows=128, progress=None, oracle_dtype=torch.float32,
+                 gemm=None, b_max=8, with_injection=True, max_rows=128, progress=None, oracle_dtype=torch.float64,
                  max_ctx=None):
     """Prefill both sides with the same prompt, then step both `n_steps` times from the same
-    committed state, comparing tokens, path, drafts and all logits after every step.  Every
+    committed state, comparing tokens, path, drafts and all logits after every step (the oracle
+    in fp64 unless the caller asks for fp32, which the full-size models do for time).  Every
     third step injects candidates built from the oracle's own greedy continuation so that
     acceptance lengths above one occur with untrained maps.
 
@@ -161,14 +162,14 @@ def run_lockstep(cfg, weights_gpu, tree: synth.Tree, *, prompt_len: int, n_steps
 
 
 def run_lockstep_batch(cfg, weights_gpu, tree: synth.Tree, *, prompt_lens, n_steps: int, tol: float, b_max=8,
-                       max_rows=None, progress=None):
+                       max_rows=None, progress=None, oracle_dtype=torch.float64):
     """Several sequences decoded side by side by one engine against one oracle per sequence.
     Every step drives both sides with the same candidates, taken from the oracle's state (its
     drafts, or its own greedy continuation planted along the last-child chain on alternating
     steps), so that what the library drafted never feeds forward: its tokens, path, drafts and
     all logits are compared after each step, with the same near-tie rule as `run_lockstep`."""
     B, N, k = len(prompt_lens), tree.n_nodes, cfg.k
-    base = make_oracle(cfg, cpu_weights(weights_gpu), b_max=b_max)
+    base = make_oracle(cfg, cpu_weights(weights_gpu), dtype=oracle_dtype, b_max=b_max)
     orcs = [base] + [base.fork() for _ in range(B - 1)]
     n_anchor = sum(tree.anchor)
     eng = make_engine(cfg, weights_gpu, max_ctx=max(prompt_lens) + (k + 1) * (n_steps + 2) + 8, max_batch=B,

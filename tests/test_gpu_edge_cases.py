@@ -103,7 +103,7 @@ def test_one_token_prompt_and_full_context(progress):
     from paper_2410_20488_amd.binding import FirpError
     cfg = synth.CONFIGS["tiny"]
     w = synth.make_weights(cfg, DEV)
-    orc = make_oracle(cfg, cpu_weights(w))
+    orc = make_oracle(cfg, cpu_weights(w), dtype=torch.float64)
     eng = make_engine(cfg, w, max_ctx=12, max_nodes=4, max_rows=16)
     tree = synth.chain_tree(3, "root")
     args = dict(parent=list(tree.parent), rank=list(tree.rank), anchor=list(tree.anchor))

@@ -1,6 +1,7 @@
 """Parity at the benchmark's full sizes: the LLaMA-2-7B- and 13B-shaped models at full depth,
 their prompts and draft trees, in the launch configuration bench.py times, against the CPU
-oracle run on the same weights (all logits of every step, tokens, path, drafts)."""
+oracle run on the same weights (all logits of every step, tokens, path, drafts).  At these sizes the
+oracle computes in fp32 (a full-depth fp64 run takes minutes); the small-model tests use fp64."""
 import pytest
 import torch
 
@@ -24,7 +25,7 @@ def test_full_depth_model_matches_oracle(name, prompt_len, n_steps, layers, prog
     w = synth.make_weights(cfg, dev)
     tree = synth.workload_tree(name)
     rep, eng, orc = run_lockstep(cfg, w, tree, prompt_len=prompt_len, n_steps=n_steps, tol=2e-2,
-                                 progress=progress, max_rows=128)
+                                 progress=progress, max_rows=128, oracle_dtype=torch.float32)
     progress(f"{name}: max logit err {rep.max_logit_err:.3e}, ties {rep.tie_ambiguous}, "
              f"accepted histogram {rep.accepted_hist}")
     assert rep.steps == n_steps
@@ -42,7 +43,7 @@ def test_34b_widths_batch_of_four(progress):
     w = synth.make_weights(cfg, dev)
     tree = synth.workload_tree("34b")
     rep, eng, orcs = run_lockstep_batch(cfg, w, tree, prompt_lens=[96, 17, 64, 130], n_steps=4, tol=2e-2,
-                                        progress=progress)
+                                        progress=progress, oracle_dtype=torch.float32)
     progress(f"34b widths: max logit err {rep.max_logit_err:.3e}, ties {rep.tie_ambiguous}, "
              f"accepted histogram {rep.accepted_hist}")
     assert rep.steps == 4

@@ -25,7 +25,7 @@ def test_train_forward_matches_oracle(name, layers, n, tol_logit, tol_kl, progre
     if layers is not None:
         cfg = dataclasses.replace(cfg, firp_layers=layers[:cfg.k])
     w = synth.make_weights(cfg, DEV, with_bias=True)
-    orc = make_oracle(cfg, cpu_weights(w))
+    orc = make_oracle(cfg, cpu_weights(w), dtype=torch.float64)
     eng = make_engine(cfg, w, max_ctx=64, max_nodes=8, max_rows=2 * n)
     toks = synth.prompt_tokens(cfg.seed + 3, n, cfg.vocab).tolist()
     for step in range(1, cfg.k + 1):
@@ -50,7 +50,7 @@ def test_train_forward_state_rules(progress):
     eng = make_engine(cfg, w, max_ctx=64, max_nodes=8, max_rows=32)
     toks = synth.prompt_tokens(5, 12, cfg.vocab).tolist()
     loss0, _ = eng.train_forward(toks, 1)
-    orc = make_oracle(cfg, cpu_weights(w))
+    orc = make_oracle(cfg, cpu_weights(w), dtype=torch.float64)
     first = eng.prefill([toks])
     assert first == [orc.prefill(toks)]
     with pytest.raises(FirpError):
