@@ -11,8 +11,8 @@
 //    vector cache tracks few outstanding lines per CU and stalls on exactly that pattern.
 //    Loads for three stages ahead are in flight while the current one is multiplied;
 //  * the activations are the small operand: a stage's [16*NT rows][64 k] tile of both planes
-//    (hi and lo bf16, see Act) is staged once per workgroup through LDS (double-buffered, row
-//    pitch 144 B so that 128-bit reads of 8 consecutive rows hit distinct banks) and shared by
+//    (hi and lo bf16, see Act) is staged once per workgroup through LDS (double-buffered,
+//    128-byte rows with the 16-byte pieces XOR-swizzled by the row number) and shared by
 //    the workgroup's waves;
 //  * fp32 accumulation in the MFMA accumulators; rows of X beyond `rows` and rows of W beyond
 //    `n` are read from clamped addresses and never stored;
@@ -32,7 +32,7 @@ typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
 
 namespace {
 constexpr int KC = 64;       // k elements per stage
-constexpr int PITCH = 144;   // bytes per LDS row: 128 data + 16 pad
+constexpr int PITCH = 128;   // bytes per LDS row of the X tile (64 columns); no padding, see below
 
 __device__ __forceinline__ bf16x8_t as_bf16x8(u32x4_t v) { return __builtin_bit_cast(bf16x8_t, v); }
 }  // namespace
@@ -75,10 +75,13 @@ __global__ __launch_bounds__(64 * NW, 2) void k_gemm_mfma(const bf16* __restrict
     int plane = c / (XROWS * 8), xrow = (c % (XROWS * 8)) >> 3;
     int row = min(xrow, rows - 1);
     xp[i] = (const char*)(plane ? xlo : xhi) + ((size_t)row * ldx + k_begin) * 2 + (c & 7) * 16;
-    xlds[i] = plane * PLANE + xrow * PITCH + (c & 7) * 16;
+    xlds[i] = plane * PLANE + xrow * PITCH + (((c & 7) ^ (xrow & 7)) * 16);
     xck[i] = c & 7;
   }
-  const int blds = r16 * PITCH + kb * 16;
+  // 16-byte piece p of row r sits at slot p ^ (r % 8) of the row: the fragment reads (16 rows x one
+  // piece per k-block) and the staging writes (8 pieces of a row per 8 lanes) are both free of
+  // bank conflicts, which padded rows are not (measured: 144-byte rows read at half the rate)
+  const int blds = r16 * PITCH + ((kb ^ (r16 & 7)) * 16);
 
   // (the padding of the copy is zero, so the last stage of a ragged K needs no guard here)
   auto load_w = [&](u32x4_t (&a)[MT][2], int stage) {
@@ -135,7 +138,7 @@ __global__ __launch_bounds__(64 * NW, 2) void k_gemm_mfma(const bf16* __restrict
       bf16x8_t bh[NT], bl[NT];
 #pragma unroll
       for (int nt = 0; nt < NT; ++nt) {
-        const unsigned char* bp = buf + blds + nt * 16 * PITCH + j * 64;
+        const unsigned char* bp = buf + (blds ^ (j * 64)) + nt * 16 * PITCH;
         bh[nt] = as_bf16x8(*(const u32x4_t*)bp);
         bl[nt] = as_bf16x8(*(const u32x4_t*)(bp + PLANE));
       }

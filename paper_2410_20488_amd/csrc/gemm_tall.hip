@@ -45,7 +45,9 @@ __device__ __forceinline__ bf16x8_t as_bf16x8(u32x4_t v) { return __builtin_bit_
 // a direct load it knows of (it cannot tell the LDS buffers apart), which would drain the weight
 // loads in flight with it.  The waits for these loads are therefore explicit (wait_vmcnt).
 __device__ __forceinline__ void load_to_lds_16(const void* base, unsigned off, unsigned lds) {
-  asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1" : : "v"(off), "s"(base), "s"(lds) : "memory");
+  // (one wait state between the scalar write of M0 and the instruction that reads it: the hazard
+  // the compiler pads for in its own code and cannot see inside an asm statement)
+  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" : : "v"(off), "s"(base), "s"(lds) : "memory");
 }
 
 // Workgroup barrier after this wave's LDS writes have completed.  (Not __syncthreads(): no fence
@@ -156,7 +158,8 @@ __global__ __launch_bounds__(512, 2) void k_gemm_tall(const bf16* __restrict__ x
   const int brow = xg * XT * 2048 + (r16 >> 3) * 1024 + (r16 & 7) * 128;
   const int bcol[2] = {((kb) ^ (r16 & 7)) * 16, ((4 + kb) ^ (r16 & 7)) * 16};
 
-  auto half = [&](auto parity, unsigned char* xcur, unsigned char* xnext, u32x4_t (&cur)[2], u32x4_t (&nxt)[2], int hs) {
+  auto half = [&](auto parity, unsigned char* xcur, unsigned char* xnext, u32x4_t (&cur)[2], u32x4_t (&nxt)[2], int hs,
+                  bool live) {
     constexpr int P = decltype(parity)::value;
     unsigned char* wbuf = wb[P];
 #pragma unroll
@@ -165,6 +168,7 @@ __global__ __launch_bounds__(512, 2) void k_gemm_tall(const bf16* __restrict__ x
     load_w(nxt, min(hs + 3, lasth));
     if constexpr (P == 0) wait_vmcnt<4>();
     lds_barrier();
+    if (!live) return;   // a half-stage past the end: its loads, waits and barrier only (see below)
     bf16x8_t a[MW];
 #pragma unroll
     for (int mt = 0; mt < MW; ++mt) a[mt] = as_bf16x8(*(const u32x4_t*)(wbuf + arow + mt * 1024));
@@ -184,16 +188,17 @@ __global__ __launch_bounds__(512, 2) void k_gemm_tall(const bf16* __restrict__ x
 
   std::integral_constant<int, 0> even;
   std::integral_constant<int, 1> odd;
-  int hs = 0;
-  for (; hs + 4 <= nh; hs += 4) {
-    half(even, xb0, xb1, w0, w3, hs);
-    half(odd, xb0, xb1, w1, w0, hs + 1);
-    half(even, xb1, xb0, w2, w1, hs + 2);
-    half(odd, xb1, xb0, w3, w2, hs + 3);
-  }
-  if (hs < nh) {   // nh is even: one more stage
-    half(even, xb0, xb1, w0, w3, hs);
-    half(odd, xb0, xb1, w1, w0, hs + 1);
+  // The explicit waits count loads in program order, so every half-stage must issue exactly the
+  // loads written here.  There is therefore no peeled tail (in one, the compiler drops the W loads
+  // whose registers nobody reads any more, and "at most 4 outstanding" then no longer covers the
+  // last X loads - seen as rare wrong values in the last rows of a tile): an odd stage count runs
+  // one more stage of loads, waits and barriers without the multiplications.
+  for (int hs = 0; hs < nh; hs += 4) {
+    const bool live = hs + 2 < nh;   // nh is even
+    half(even, xb0, xb1, w0, w3, hs, true);
+    half(odd, xb0, xb1, w1, w0, hs + 1, true);
+    half(even, xb1, xb0, w2, w1, hs + 2, live);
+    half(odd, xb1, xb0, w3, w2, hs + 3, live);
   }
   wait_vmcnt<0>();   // nothing of this workgroup may still be on its way into LDS when it ends
 

@@ -66,3 +66,17 @@ def test_mfma_projection_random_shapes(rows, n, K):
     y = binding.debug_gemm(x, w, kind=1).cpu().double()
     ref = x.cpu().double() @ w.cpu().double().T
     assert float((y - ref).abs().max() / ref.std()) < 2e-4
+
+
+@pytest.mark.parametrize("rows,n,K,repeats", [(256, 44032, 8192, 300), (200, 27648, 5120, 300), (67, 27648, 5120, 200),
+                                             (256, 8192, 22016, 200)])   # an odd number of stages per workgroup
+def test_projection_is_bit_repeatable(rows, n, K, repeats):
+    """The kernels are deterministic (fixed summation order, no atomics): every launch on the same
+    operands must give the same bits.  Hundreds of launches of the largest shapes - some 10^8 wave-level
+    loads into LDS for the 256-row one - would show a missed wait or hazard as a rare mismatch."""
+    x, w = _inputs(rows, n, K, torch.bfloat16)
+    first = binding.debug_gemm(x, w, kind=1)
+    bad = 0
+    for _ in range(repeats):
+        bad += int(not torch.equal(binding.debug_gemm(x, w, kind=1), first))
+    assert bad == 0, f"{bad} of {repeats} launches differ from the first"
