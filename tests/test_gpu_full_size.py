@@ -121,25 +121,30 @@ def test_13b_full_depth_decoding_is_lossless(progress):
     assert hist[cfg.k + 1] > 0 and ties <= 3
 
 
-def test_batched_step_is_bit_repeatable(progress):
-    """The step is deterministic (no atomics, fixed summation orders): prefill plus two steps of the
-    34B-width batch of four, thirty times on one engine, must give the same logits bit for bit.  The
+@pytest.mark.parametrize("case", ["34b_batch4", "13b_all_anchors"])
+def test_step_is_bit_repeatable(case, progress):
+    """The step is deterministic (no atomics, fixed summation orders): prefill plus two steps, many
+    times on one engine, must give the same logits bit for bit - for the 34B-width batch of four
+    (4 layers) and for the 13B shape at full depth with every node an anchor (256 rows).  The
     activations a projection reads are freshly written by the kernel before it here, unlike in the
     per-kernel test: this is the run that showed a wait in the 129..256-row projection to be too weak
     for an odd number of stages (wrong values in a tile's last rows every other run)."""
     import numpy as np
     from tests.gpu_common import make_engine
     dev = torch.device("cuda:0")
-    cfg = synth.scaled_config(synth.CONFIGS["34b"], 4, 2)
+    if case == "34b_batch4":
+        cfg, lens, anchors, repeats = synth.scaled_config(synth.CONFIGS["34b"], 4, 2), [96, 17, 64, 130], "root", 30
+    else:
+        cfg, lens, anchors, repeats = synth.CONFIGS["13b"], [300], "all", 8
     w = synth.make_weights(cfg, dev)
-    tree = synth.workload_tree("34b")
-    lens = [96, 17, 64, 130]
+    tree = synth.workload_tree("13b", anchors)
+    n_rows = tree.n_nodes + cfg.k * sum(tree.anchor)
     prompts = [synth.prompt_tokens(cfg.seed + 31, n, cfg.vocab, stream=b).tolist() for b, n in enumerate(lens)]
     args = (list(tree.parent), list(tree.rank), list(tree.anchor))
-    eng = make_engine(cfg, w, max_ctx=max(lens) + 40, max_batch=4, max_nodes=tree.n_nodes,
-                      max_rows=tree.n_nodes + cfg.k, b_max=8)
+    eng = make_engine(cfg, w, max_ctx=max(lens) + 40, max_batch=len(lens), max_nodes=tree.n_nodes, max_rows=n_rows,
+                      b_max=8)
     ref, bad = None, 0
-    for it in range(30):
+    for it in range(repeats):
         outs = [np.array(eng.prefill(prompts))]
         for _ in range(2):
             eng.step(*args)
@@ -148,5 +153,5 @@ def test_batched_step_is_bit_repeatable(progress):
             ref = outs
         elif not all(np.array_equal(a, b) for a, b in zip(outs, ref)):
             bad += 1
-    progress(f"repeatability: {bad} of 29 runs differ from the first")
+    progress(f"repeatability {case}: {bad} of {repeats - 1} runs differ from the first")
     assert bad == 0
