@@ -6,8 +6,8 @@
 // W in the fragment-major copy, X as hi/lo bf16 planes, split-K partial sums.  With this many
 // rows the step is no longer bound by the HBM stream of W alone: per byte of W a workgroup also
 // pulls the X tile through the CU's vector cache (which keeps only about 80 lines in flight,
-// whether they come from HBM or from L2) and reads the activation fragments from LDS (about
-// 80 B per clock per CU for 128-bit reads, measured).  Both grow with rows / (rows of W per
+// whether they come from HBM or from L2) and reads the activation fragments from LDS (which
+// delivers 128-bit reads at full rate only from a conflict-free layout).  Both grow with rows / (rows of W per
 // workgroup), and the LDS reads also with 1 / (rows of W per wave).  So:
 //  * a workgroup of 8 waves owns 256 rows of W and up to 256 rows of X: the largest tile whose
 //    accumulators (a quarter of a MiB) fit the register file with two waves per SIMD;
