@@ -121,7 +121,7 @@ def test_13b_full_depth_decoding_is_lossless(progress):
     assert hist[cfg.k + 1] > 0 and ties <= 3
 
 
-@pytest.mark.parametrize("case", ["34b_batch4", "13b_all_anchors"])
+@pytest.mark.parametrize("case", ["34b_batch4", "13b_all_anchors", "13b_root_anchor"])
 def test_step_is_bit_repeatable(case, progress):
     """The step is deterministic (no atomics, fixed summation orders): prefill plus two steps, many
     times on one engine, must give the same logits bit for bit - for the 34B-width batch of four
@@ -134,8 +134,10 @@ def test_step_is_bit_repeatable(case, progress):
     dev = torch.device("cuda:0")
     if case == "34b_batch4":
         cfg, lens, anchors, repeats = synth.scaled_config(synth.CONFIGS["34b"], 4, 2), [96, 17, 64, 130], "root", 30
-    else:
+    elif case == "13b_all_anchors":
         cfg, lens, anchors, repeats = synth.CONFIGS["13b"], [300], "all", 8
+    else:
+        cfg, lens, anchors, repeats = synth.CONFIGS["13b"], [300], "root", 8
     w = synth.make_weights(cfg, dev)
     tree = synth.workload_tree("13b", anchors)
     n_rows = tree.n_nodes + cfg.k * sum(tree.anchor)
