@@ -92,3 +92,31 @@ def test_7b_widths_4_layers_full_tree(dev, progress):
                                  progress=progress)
     progress(f"7b/4 layers: max logit err {rep.max_logit_err:.3e}, ties {rep.tie_ambiguous}")
     compare_cache(eng, orc, cfg)
+
+
+@pytest.mark.parametrize("name,seed", [("tiny_bf16", 3), ("tiny_gqa", 5), ("tiny", 7)])
+def test_small_model_steps_are_bit_repeatable(dev, progress, name, seed):
+    """Prefill and four steps with an irregular tree (two sequences of different length), forty times
+    on one engine: identical tokens and identical logits, bit for bit, every time."""
+    import numpy as np
+    from tests.gpu_common import make_engine
+    cfg = synth.CONFIGS[name]
+    w = synth.make_weights(cfg, dev, with_bias=True)
+    tree = synth.random_tree(seed, 19, cfg.k, 4, 0.6)
+    n_rows = tree.n_nodes + cfg.k * sum(tree.anchor)
+    prompts = [synth.prompt_tokens(seed, 150, cfg.vocab).tolist(), synth.prompt_tokens(seed, 9, cfg.vocab, stream=1).tolist()]
+    args = (list(tree.parent), list(tree.rank), list(tree.anchor))
+    eng = make_engine(cfg, w, max_ctx=220, max_batch=2, max_nodes=tree.n_nodes, max_rows=n_rows, b_max=8)
+    ref, bad = None, 0
+    for it in range(40):
+        outs = [np.array(eng.prefill(prompts))]
+        for _ in range(4):
+            toks = eng.step(*args)
+            outs.append(np.array([t + [-1] * (cfg.k + 1 - len(t)) for t in toks]))
+            outs.append(eng.last_logits().copy())
+        if ref is None:
+            ref = outs
+        elif not all(np.array_equal(a, b) for a, b in zip(outs, ref)):
+            bad += 1
+    progress(f"repeatability {name}: {bad} of 39 runs differ from the first")
+    assert bad == 0
