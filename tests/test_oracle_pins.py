@@ -297,17 +297,19 @@ def test_real_rows_do_not_depend_on_pseudo_rows_or_non_ancestors():
     o2 = make_oracle(cfg, w2, dtype=F64)
     o2.prefill(prompt)
     alt = o2.step(**_tree_args(synth.with_anchors(tree, "root")), node_tokens=cand).logits
-    assert torch.equal(base[:tree.n_nodes], alt[:tree.n_nodes])
+    # (equal in exact arithmetic; a library matmul may round its fp64 sums differently for another
+    # number of rows, so the comparison allows for that and no more)
+    assert (base[:tree.n_nodes] - alt[:tree.n_nodes]).abs().max() < 1e-12
     n_anchor_all = tree.n_nodes
     root_rows = [tree.n_nodes + i * n_anchor_all for i in range(cfg.k)]   # root's pseudo rows among all anchors'
-    assert not torch.equal(base[root_rows], alt[tree.n_nodes:])
+    assert (base[root_rows] - alt[tree.n_nodes:]).abs().max() > 1e-3
     # a node outside the ancestor set of node 3 (= child of node 1): change node 2's token
     cand2 = list(cand)
     cand2[2] = (cand2[2] + 1) % cfg.vocab
     o.prefill(prompt)
     alt2 = o.step(**_tree_args(tree), node_tokens=cand2).logits
     assert tree.parent[3] == 1
-    assert torch.equal(base[3], alt2[3]) and not torch.equal(base[2], alt2[2])
+    assert (base[3] - alt2[3]).abs().max() < 1e-12 and (base[2] - alt2[2]).abs().max() > 1e-3
 
 
 def test_position_ids_of_tree_and_pseudo_rows():
