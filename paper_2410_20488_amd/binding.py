@@ -186,6 +186,9 @@ class Engine:
         if nbytes == 0:
             raise FirpError(-1, "invalid model description")
         self.workspace = torch.empty(nbytes + 256, dtype=torch.uint8, device=dev)
+        if os.environ.get("FIRP_POISON_WORKSPACE"):
+            # test aid: a workspace of NaN bit patterns shows any read of memory the library has not written
+            self.workspace.fill_(0xFF)
         base = (self.workspace.data_ptr() + 255) // 256 * 256
         self.stream = stream if stream is not None else torch.cuda.current_stream(dev)
         ctx = C.c_void_p()
@@ -313,6 +316,8 @@ def debug_gemm(x: torch.Tensor, w: torch.Tensor, kind: int) -> torch.Tensor:
     y = torch.empty(rows, n, dtype=torch.float32, device=x.device)
     nbytes = lib.firp_gemm_workspace_bytes(rows, n, kd)
     ws = torch.empty(nbytes + 256, dtype=torch.uint8, device=x.device)
+    if os.environ.get("FIRP_POISON_WORKSPACE"):
+        ws.fill_(0xFF)
     base = (ws.data_ptr() + 255) // 256 * 256
     rc = lib.firp_debug_gemm(x.data_ptr(), w.data_ptr(), y.data_ptr(), rows, n, kd,
                              1 if w.dtype == torch.bfloat16 else 0, kind, base, nbytes,
