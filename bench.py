@@ -81,7 +81,7 @@ def cpu_baseline(cfg, weights_gpu, tree, prompt, budget_note: str):
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=64)
+    ap.add_argument("--steps", type=int, default=128)
     ap.add_argument("--warmup", type=int, default=8)
     ap.add_argument("--config", default="13b", choices=["13b", "7b", "34b", "tiny_bf16"])
     ap.add_argument("--batch", type=int, default=1, help="independent sequences decoded side by side")
