@@ -144,10 +144,14 @@ def main() -> int:
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     tokens = 0
+    stamps = [t0]   # every step ends with its own host synchronisation (it returns the tokens)
     for _ in range(args.steps):
         tokens += sum(len(t) for t in eng.step(*targs))
+        stamps.append(time.perf_counter())
     torch.cuda.synchronize()
     t1 = time.perf_counter()
+    per_step = sorted((b - a) * 1e3 for a, b in zip(stamps, stamps[1:]))
+    pct = lambda q: per_step[min(len(per_step) - 1, int(q * len(per_step)))]
     ctx_last = eng.ctx_len()[0]
     ms_per_step = (t1 - t0) * 1e3 / args.steps
 
@@ -175,6 +179,7 @@ def main() -> int:
                                f"layer {cfg.firp_layer if cfg.firp_layers is None else list(cfg.firp_layers)}, batch {args.batch}, prompt {prompt_len} uniform-random tokens, "
                                f"{tree.n_nodes}-node draft tree, anchors={args.anchors} (T_hi={t_hi}), "
                                f"ctx {ctx_first}->{ctx_last}"},
+        "ms_per_step_p10_median_p90": [round(pct(0.1), 4), round(pct(0.5), 4), round(pct(0.9), 4)],
         "step_algorithmic_GB": round(step_bytes / 1e9, 3),
         "step_achieved_GBps": round(step_gbs, 1),
         "step_frac_of_hbm_peak": round(step_gbs / HBM_PEAK_GBS, 4),
