@@ -88,7 +88,8 @@ __global__ __launch_bounds__(64 * NW, 2) void k_gemm_mfma(const bf16* __restrict
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-      for (int j = 0; j < 2; ++j) a[mt][j] = *(const u32x4_t*)(wp[mt] + (size_t)stage * 2048 + j * 1024);
+      for (int j = 0; j < 2; ++j)
+        a[mt][j] = __builtin_nontemporal_load((const u32x4_t*)(wp[mt] + (size_t)stage * 2048 + j * 1024));
   };
   auto load_x = [&](u32x4_t (&x)[XP], int stage) {
 #pragma unroll

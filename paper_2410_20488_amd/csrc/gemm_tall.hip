@@ -122,7 +122,7 @@ __global__ __launch_bounds__(512, 2) void k_gemm_tall(const bf16* __restrict__ x
 
   auto load_w = [&](u32x4_t (&a)[2], int hs) {
 #pragma unroll
-    for (int i = 0; i < 2; ++i) a[i] = *(const u32x4_t*)(wsrc[i] + (size_t)hs * 1024 + woff);
+    for (int i = 0; i < 2; ++i) a[i] = __builtin_nontemporal_load((const u32x4_t*)(wsrc[i] + (size_t)hs * 1024 + woff));
   };
   auto dma_x = [&](unsigned char* xbuf, int st) {
     const unsigned l0 = lds_address(xbuf) + wave_u * 1024;

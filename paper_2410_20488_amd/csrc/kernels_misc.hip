@@ -583,7 +583,14 @@ void launch_reduce_partials(const Partial& p, float* y, int rows, hipStream_t s)
 
 // ------------------------------------------------------------------------------------------
 // A plain streaming read (the measured ceiling the step's bandwidth is compared with): every
-// wave reads 1 KiB per instruction, eight loads in flight per lane, nothing else happens.
+// wave reads 1 KiB per instruction, eight loads in flight per lane, nothing else happens.  The
+// loads carry the non-temporal hint like the projection's weight loads (measured: 6.9 TB/s
+// against 6.1 TB/s without it).
+__device__ __forceinline__ uint4 nt_load16(const uint4* p) {
+  typedef unsigned int u4 __attribute__((ext_vector_type(4)));
+  const u4 r = __builtin_nontemporal_load((const u4*)p);
+  return make_uint4(r.x, r.y, r.z, r.w);
+}
 __global__ __launch_bounds__(256) void k_stream_read(const uint4* __restrict__ src, size_t n16, unsigned* __restrict__ sink) {
   const size_t stride = (size_t)gridDim.x * blockDim.x;
   size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -591,7 +598,7 @@ __global__ __launch_bounds__(256) void k_stream_read(const uint4* __restrict__ s
   for (; i + 7 * stride < n16; i += 8 * stride) {
     uint4 v[8];
 #pragma unroll
-    for (int j = 0; j < 8; ++j) v[j] = src[i + j * stride];
+    for (int j = 0; j < 8; ++j) v[j] = nt_load16(src + i + j * stride);
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
       acc.x ^= v[j].x;
@@ -601,7 +608,7 @@ __global__ __launch_bounds__(256) void k_stream_read(const uint4* __restrict__ s
     }
   }
   for (; i < n16; i += stride) {
-    uint4 v = src[i];
+    uint4 v = nt_load16(src + i);
     acc.x ^= v.x;
     acc.y ^= v.y;
     acc.z ^= v.z;
