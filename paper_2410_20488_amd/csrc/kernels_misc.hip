@@ -582,32 +582,41 @@ void launch_reduce_partials(const Partial& p, float* y, int rows, hipStream_t s)
 }
 
 // ------------------------------------------------------------------------------------------
-// A plain streaming read (the measured ceiling the step's bandwidth is compared with): every
-// wave reads 1 KiB per instruction, eight loads in flight per lane, nothing else happens.  The
-// loads carry the non-temporal hint like the projection's weight loads (measured: 6.9 TB/s
+// A plain streaming read (the measured ceiling the step's bandwidth is compared with): nothing
+// but loads.  They carry the non-temporal hint like the projection's weight loads (measured: 6.9 TB/s
 // against 6.1 TB/s without it).
 __device__ __forceinline__ uint4 nt_load16(const uint4* p) {
   typedef unsigned int u4 __attribute__((ext_vector_type(4)));
   const u4 r = __builtin_nontemporal_load((const u4*)p);
   return make_uint4(r.x, r.y, r.z, r.w);
 }
-__global__ __launch_bounds__(256) void k_stream_read(const uint4* __restrict__ src, size_t n16, unsigned* __restrict__ sink) {
-  const size_t stride = (size_t)gridDim.x * blockDim.x;
-  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+// Every wave walks two private contiguous runs, 1 KiB per instruction and 4 KiB ahead in each (the
+// projection's shape of traffic); what the runs leave over is read with a grid-wide stride.
+__global__ __launch_bounds__(512) void k_stream_read(const uint4* __restrict__ src, size_t n16, unsigned* __restrict__ sink) {
+  constexpr int STREAMS = 2, DEPTH = 4;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, wpb = blockDim.x >> 6;
+  const size_t nstreams = (size_t)gridDim.x * wpb * STREAMS;
+  const size_t per = n16 / nstreams / (64 * DEPTH) * (64 * DEPTH);   // 16-byte items of one run
+  const size_t s0 = ((size_t)blockIdx.x * wpb + wave) * STREAMS;
   uint4 acc = make_uint4(0, 0, 0, 0);
-  for (; i + 7 * stride < n16; i += 8 * stride) {
-    uint4 v[8];
+  for (size_t off = 0; off < per; off += 64 * DEPTH) {
+    uint4 v[STREAMS][DEPTH];
 #pragma unroll
-    for (int j = 0; j < 8; ++j) v[j] = nt_load16(src + i + j * stride);
+    for (int st = 0; st < STREAMS; ++st)
 #pragma unroll
-    for (int j = 0; j < 8; ++j) {
-      acc.x ^= v[j].x;
-      acc.y ^= v[j].y;
-      acc.z ^= v[j].z;
-      acc.w ^= v[j].w;
-    }
+      for (int j = 0; j < DEPTH; ++j) v[st][j] = nt_load16(src + (s0 + st) * per + off + j * 64 + lane);
+#pragma unroll
+    for (int st = 0; st < STREAMS; ++st)
+#pragma unroll
+      for (int j = 0; j < DEPTH; ++j) {
+        acc.x ^= v[st][j].x;
+        acc.y ^= v[st][j].y;
+        acc.z ^= v[st][j].z;
+        acc.w ^= v[st][j].w;
+      }
   }
-  for (; i < n16; i += stride) {
+  for (size_t i = nstreams * per + (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16;
+       i += (size_t)gridDim.x * blockDim.x) {
     uint4 v = nt_load16(src + i);
     acc.x ^= v.x;
     acc.y ^= v.y;
@@ -618,7 +627,7 @@ __global__ __launch_bounds__(256) void k_stream_read(const uint4* __restrict__ s
 }
 
 void launch_stream_read(const void* src, size_t bytes, unsigned* sink, hipStream_t s) {
-  hipLaunchKernelGGL(k_stream_read, dim3(256 * 8), dim3(256), 0, s, (const uint4*)src, bytes / 16, sink);
+  hipLaunchKernelGGL(k_stream_read, dim3(512), dim3(512), 0, s, (const uint4*)src, bytes / 16, sink);
 }
 
 }  // namespace firp
