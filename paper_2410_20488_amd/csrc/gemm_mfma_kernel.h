@@ -132,10 +132,18 @@ __global__ __launch_bounds__(64 * NW, 2) void k_gemm_mfma(const bf16* __restrict
 #pragma unroll
     for (int i = 0; i < XP; ++i) *(u32x4_t*)(buf + xlds[i]) = xc[i];
     load_x(xc, min(st + XAHEAD, last));
-    load_w(nxt3, min(st + 3, last));
     __syncthreads();
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
+      if (j == 1) {
+        // The W loads go out in the middle of the stage's products, not in front of the barrier:
+        // the vector cache's queue is full most of the time, an issuing wave waits for room in
+        // it, and here that wait overlaps with the other waves' products instead of holding up
+        // the whole workgroup at the barrier (measured at 67 rows: 3-8 % per 13B projection).
+        __builtin_amdgcn_sched_barrier(0);
+        load_w(nxt3, min(st + 3, last));
+        __builtin_amdgcn_sched_barrier(0);
+      }
       bf16x8_t bh[NT], bl[NT];
 #pragma unroll
       for (int nt = 0; nt < NT; ++nt) {
