@@ -22,7 +22,7 @@ HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E bandwidth
 # HBM bytes moved per algorithmic weight byte by the projection kernel at the 13B shapes,
 # weighted by each shape's share of a step: (FETCH_SIZE + WRITE_SIZE) / weights from the
 # rocprofv3 --pmc runs summarised in profiles/k_gemm_mfma_13b_shapes_hbm_traffic.md
-GEMM_TRAFFIC_RATIO_13B = 1.173
+GEMM_TRAFFIC_RATIO_13B = 1.171
 
 
 def algorithmic_bytes(cfg, n_nodes: int, t_hi: int, ctx: int, batch: int = 1) -> float:
