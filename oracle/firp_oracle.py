@@ -38,8 +38,10 @@ Pins (tests/test_oracle_pins.py): the decoder against the HuggingFace LLaMA impl
 the paper builds on and against torch's library attention / rms_norm; RoPE's relative-
 position property; tree attention against brute-force per-path causal runs; pseudo rows
 against a brute-force chain with hand-inserted rows; losslessness against cache-free
-sequential greedy decoding; forced-acceptance cases; commit == prefill; the training forward
-against per-position causal chains and the library KL routine.
+sequential greedy decoding; forced-acceptance cases; commit == prefill; candidate fill against
+a hand-written tree and hand-written draft lists; the next drafts against a plain Python ranking
+of the brute-force chain's pseudo-row logits of the node that ends the accepted path (ties
+planted); the training forward against per-position causal chains and the library KL routine.
 """
 from __future__ import annotations
 

@@ -458,3 +458,119 @@ def test_training_loss_vanishes_when_the_pseudo_state_is_the_true_one():
     o2 = make_oracle(cfg, w2, dtype=F64)
     loss, kl, _ = o2.train_forward(toks, 1)
     assert kl.shape == (1,) and abs(loss) < 1e-12
+
+
+# ------------------------------------------------------------------ candidate fill and draft selection
+
+
+def test_candidate_fill_from_hand_written_drafts():
+    """Inference stage ("merging their common ancestors"): node v of the tree carries the
+    candidate drafts[level(v) - 1][rank(v)] and the root carries the last emitted token.  Tree
+    and drafts are written by hand here, and so is the expected list."""
+    o, _ = _micro()
+    o.prefill(synth.prompt_tokens(81, 5, MICRO.vocab).tolist())
+    o.root_token = 5
+    o.drafts = [[10, 11, 12], [20, 21, 22]]
+    #           root | level 1: ranks 0, 1, 2 | level 2 below node 1: ranks 0, 1; below node 2: rank 1;
+    #           below node 3: rank 2
+    parent = [-1, 0, 0, 0, 1, 1, 2, 3]
+    rank = [0, 0, 1, 2, 0, 1, 1, 2]
+    r = o.step(parent=parent, rank=rank, anchor=[1] + [0] * 7)
+    assert r.node_tokens == [5, 10, 11, 12, 20, 21, 21, 22]
+    assert not r.ran_root_only
+
+
+def _independent_top_b(row: torch.Tensor, b: int):
+    """Ids of the b largest entries, larger value first, equal values by ascending id: written
+    with a Python sort on (value, id) pairs, no tensor sort."""
+    vals = row.tolist()
+    return sorted(range(len(vals)), key=lambda t: (-vals[t], t))[:b]
+
+
+def _chain_pseudo_logits(brute, w, cfg, seq):
+    """Logits of the k mapped rows of a plain causal chain over `seq`: row i = W_i h + b_i of the
+    last position's residual stream entering layer t_i, appended there at position +i."""
+    empty = torch.zeros(0, cfg.n_kv_heads, cfg.head_dim, dtype=F64)
+    n = len(seq)
+    x = brute._embed(seq)
+    for layer in range(cfg.n_layers + 1):
+        for i in range(cfg.k):
+            if cfg.layers[i] == layer:
+                x = torch.cat([x, (w["proj_w"][i].double() @ x[n - 1] + w["proj_b"][i].double())[None]])
+        if layer == cfg.n_layers:
+            break
+        m = x.shape[0]
+        x, _, _ = brute._layer(layer, x, torch.arange(m), empty, empty, torch.tril(torch.ones(m, m, dtype=torch.bool)))
+    return brute._logits(x)[n:]
+
+
+@pytest.mark.parametrize("layers", [None, (1, 3)])
+def test_next_drafts_are_the_top_b_of_the_path_end_pseudo_rows(layers):
+    """Inference stage: the next tree is generated "on the basis of S": level i of it holds the
+    b most probable tokens of pseudo hidden state i of the node that ENDS the accepted path, the
+    most probable first.  The expectation comes from a brute-force causal chain over prompt +
+    accepted path with the mapped rows inserted by hand, ranked by a plain Python sort; the
+    step after that must place exactly those ids on the tree (hand-indexed)."""
+    cfg = MICRO if layers is None else dataclasses.replace(MICRO, firp_layers=layers)
+    b = 5
+    w = synth.make_weights(cfg, "cpu", with_bias=True, std=0.08)
+    o = make_oracle(cfg, w, dtype=F64, b_max=b)
+    brute = make_oracle(cfg, w, dtype=F64)
+    prompt = synth.prompt_tokens(83, 7, cfg.vocab).tolist()
+    g = o.greedy(prompt, 4)
+    assert o.prefill(prompt) == g[0]
+    # the drafts of the prefill's root-only step: the chain ends at the last prompt token
+    want0 = [_independent_top_b(row, b) for row in _chain_pseudo_logits(brute, w, cfg, prompt)]
+    assert o.drafts == want0
+    # a tree with every node an anchor; the true continuation sits on non-first siblings, so
+    # the path ends at a non-root anchor
+    tree = synth.full_tree((3, 2), "all")
+    cand = _random_candidates(7, tree.n_nodes, cfg.vocab)
+    for v in range(1, tree.n_nodes):
+        if cand[v] in g:
+            cand[v] = (cand[v] + 1) % cfg.vocab if (cand[v] + 1) % cfg.vocab not in g else (cand[v] + 2) % cfg.vocab
+    kids0 = [v for v in range(tree.n_nodes) if tree.parent[v] == 0]
+    cand[kids0[1]] = g[1]
+    kids1 = [v for v in range(tree.n_nodes) if tree.parent[v] == kids0[1]]
+    cand[kids1[-1]] = g[2]
+    r = o.step(**_tree_args(tree), node_tokens=cand)
+    assert r.path == [0, kids0[1], kids1[-1]] and r.tokens == g[1:4]
+    seq = prompt + [g[0], cand[kids0[1]], cand[kids1[-1]]]      # the root carries the first generated token
+    want = [_independent_top_b(row, b) for row in _chain_pseudo_logits(brute, w, cfg, seq)]
+    assert r.drafts == want and o.drafts == want
+    # ... and they are not the root's, nor any other anchor's
+    for other in ([0], [0, kids0[1]], [0, kids0[0]]):
+        other_seq = prompt + [g[0]] + [cand[u] for u in other[1:]]
+        assert [_independent_top_b(row, b) for row in _chain_pseudo_logits(brute, w, cfg, other_seq)] != want
+    # the best candidate of each level is the argmax of its pseudo row
+    for i in range(cfg.k):
+        assert want[i][0] == int(torch.argmax(_chain_pseudo_logits(brute, w, cfg, seq)[i]))
+    # next step, no injection: the tree is filled from these lists by (level, rank)
+    tree2 = synth.Tree((-1, 0, 0, 0, 1, 1, 3), (0, 0, 2, 4, 1, 3, 0), (1, 0, 0, 0, 0, 0, 0))
+    r2 = o.step(**_tree_args(tree2))
+    assert r2.node_tokens == [g[3], want[0][0], want[0][2], want[0][4], want[1][1], want[1][3], want[1][0]]
+
+
+def test_top_b_ties_against_an_independent_sort():
+    """Equal logits: the lower token id ranks first, in the greedy token and in the draft lists
+    (checked against the Python sort above on a vocabulary with planted exact ties)."""
+    cfg = MICRO
+    w = synth.make_weights(cfg, "cpu", with_bias=True, std=0.08)
+    lm = w["lm_head"].clone()
+    lm[40] = lm[3]
+    lm[90] = lm[3]
+    lm[17] = lm[64]
+    w2 = dict(w)
+    w2["lm_head"] = lm
+    b = cfg.vocab        # the whole ranking
+    o = make_oracle(cfg, w2, dtype=F64, b_max=b)
+    prompt = synth.prompt_tokens(85, 6, cfg.vocab).tolist()
+    first = o.prefill(prompt)
+    brute = make_oracle(cfg, w2, dtype=F64)
+    assert first == _independent_top_b(brute.causal_forward(prompt)[-1], 1)[0]
+    rows = _chain_pseudo_logits(brute, w2, cfg, prompt)
+    for i in range(cfg.k):
+        want = _independent_top_b(rows[i], b)
+        assert o.drafts[i] == want
+        assert want.index(3) + 1 == want.index(40) and want.index(40) + 1 == want.index(90)
+        assert want.index(17) + 1 == want.index(64)
