@@ -243,6 +243,21 @@ firp_status firp_debug_gemm(const float *x, const void *w, float *y, int32_t row
                             int32_t k_dim, int32_t dtype, int32_t kind, void *workspace,
                             size_t workspace_bytes, void *hip_stream);
 
+/* The same projection (firp_debug_gemm with bf16 w and kind 1) for callers that cannot
+ * allocate device memory or pass a workspace: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  It calls no allocating routine.  Its scratch (operand
+ * planes, partial sums, the fragment-major copy of w) is one fixed buffer of
+ * firp_gemm_static_capacity() bytes (32 MiB) per GPU, held from the first use on that GPU until
+ * the process ends; shapes whose firp_gemm_workspace_bytes(rows, n, k_dim) exceed it are
+ * rejected with FIRP_ECAPACITY (firp_last_error(NULL) says by how much) before anything is
+ * enqueued.  x, w (bf16 [n, K]), y are DEVICE pointers of the current device; the work is
+ * enqueued on `hip_stream`.  Every call on a GPU uses that GPU's one buffer: calls that overlap
+ * on one GPU (two streams, two threads) race; calls in stream order do not.  Nothing in the
+ * buffer needs to start at zero: each call rewrites every byte it later reads. */
+size_t firp_gemm_static_capacity(void);
+firp_status firp_debug_gemm_static(const float *x, const void *w, float *y, int32_t rows, int32_t n,
+                                   int32_t k_dim, void *hip_stream);
+
 /* Measurement aid: one kernel that only reads `bytes` (>= 16, a multiple of 16 is read) of DEVICE
  * memory at `src` (16-byte aligned) on `hip_stream`; `sink` is 4 bytes of DEVICE memory it may
  * write.  Timing it over a buffer larger than every cache gives the streaming-read rate a kernel

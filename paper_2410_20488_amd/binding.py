@@ -88,6 +88,8 @@ def load_library() -> C.CDLL:
         "firp_debug_gemm_plan": (C.c_int32, [C.c_int32, C.c_int32, C.c_int32] + [C.POINTER(C.c_int32)] * 5),
         "firp_debug_gemm": (C.c_int, [vp, vp, vp, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32, vp,
                                        C.c_size_t, vp]),
+        "firp_gemm_static_capacity": (C.c_size_t, []),
+        "firp_debug_gemm_static": (C.c_int, [vp, vp, vp, C.c_int32, C.c_int32, C.c_int32, vp]),
     }
     for name, (res, args) in sig.items():
         fn = getattr(lib, name)
@@ -99,7 +101,8 @@ def load_library() -> C.CDLL:
 EXPORTED = ["firp_workspace_bytes", "firp_init", "firp_init_layers", "firp_build_tree", "firp_train_forward", "firp_prefill", "firp_step", "firp_reset", "firp_destroy",
             "firp_last_error", "firp_step_with_candidates", "firp_check_tree", "firp_debug_last_logits", "firp_debug_last_path",
             "firp_get_drafts", "firp_get_ctx_len", "firp_debug_read_cache", "firp_set_option", "firp_get_gemm_timing",
-            "firp_gemm_workspace_bytes", "firp_debug_gemm", "firp_debug_gemm_plan", "firp_debug_stream_read"]
+            "firp_gemm_workspace_bytes", "firp_debug_gemm", "firp_debug_gemm_plan", "firp_debug_stream_read",
+            "firp_gemm_static_capacity", "firp_debug_gemm_static"]
 
 
 def _i32(a) -> np.ndarray:
@@ -325,6 +328,20 @@ def debug_gemm(x: torch.Tensor, w: torch.Tensor, kind: int) -> torch.Tensor:
     if rc != 0:
         raise FirpError(rc, "firp_debug_gemm")
     return y
+
+
+def debug_gemm_static(x: torch.Tensor, w: torch.Tensor, y: torch.Tensor) -> None:
+    """y = x . w^T through the entry point that allocates nothing (bf16 w; y is the caller's)."""
+    lib = load_library()
+    assert x.dtype == torch.float32 and y.dtype == torch.float32 and w.dtype == torch.bfloat16
+    assert x.is_cuda and x.is_contiguous() and w.is_contiguous() and y.is_contiguous()
+    rows, kd = x.shape
+    n = w.shape[0]
+    assert tuple(y.shape) == (rows, n)
+    rc = lib.firp_debug_gemm_static(x.data_ptr(), w.data_ptr(), y.data_ptr(), rows, n, kd,
+                                    torch.cuda.current_stream(x.device).cuda_stream)
+    if rc != 0:
+        raise FirpError(rc, lib.firp_last_error(None).decode())
 
 
 def gemm_plan(rows: int, n: int, k_dim: int) -> dict:

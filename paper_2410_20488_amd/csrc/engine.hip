@@ -1051,6 +1051,24 @@ size_t firp_gemm_workspace_bytes(int32_t rows, int32_t n, int32_t k_dim) {
          align_up(gemm_packed_bytes(n, k_dim), 256) + 512;
 }
 
+// the MFMA projection of the standalone entries: operand planes, split-K partial sums and the
+// fragment-major copy of w live in `workspace` (>= firp_gemm_workspace_bytes)
+static void gemm_in_workspace(const float* x, const void* w, float* y, int rows, int n, int k_dim, void* workspace,
+                              hipStream_t s) {
+  size_t rp = align_up(rows, 16);
+  Act a{};
+  a.ld = k_dim;
+  a.hi = (bf16*)workspace;
+  a.lo = a.hi + rp * k_dim;
+  float* part = (float*)((char*)workspace + align_up(rp * k_dim * 2 * 2, 256));
+  void* wpk = (char*)part + align_up(rp * (size_t)n * 4 * 16, 256);
+  launch_split_act(x, rows, k_dim, a, s);
+  launch_pack_weights(wseg1(w, n), n, k_dim, wpk, s);
+  GemmPlan plan = gemm_mfma_plan(rows, n, k_dim, 0);
+  launch_gemm_mfma(a, wpk, part, n, rp * n, rows, n, k_dim, plan, s);
+  launch_reduce_partials(Partial{part, plan.S, rp * (size_t)n, n}, y, rows, s);
+}
+
 firp_status firp_debug_gemm(const float* x, const void* w, float* y, int32_t rows, int32_t n, int32_t k_dim,
                             int32_t dtype, int32_t kind, void* workspace, size_t workspace_bytes,
                             void* hip_stream) {
@@ -1063,22 +1081,50 @@ firp_status firp_debug_gemm(const float* x, const void* w, float* y, int32_t row
     if (dtype != FIRP_BF16 || !gemm_mfma_supported(rows, n, k_dim)) return FIRP_EINVAL;
     if (!workspace || (((uintptr_t)workspace) & 255) || workspace_bytes < firp_gemm_workspace_bytes(rows, n, k_dim))
       return FIRP_ECAPACITY;
-    size_t rp = align_up(rows, 16);
-    Act a{};
-    a.ld = k_dim;
-    a.hi = (bf16*)workspace;
-    a.lo = a.hi + rp * k_dim;
-    float* part = (float*)((char*)workspace + align_up(rp * k_dim * 2 * 2, 256));
-    void* wpk = (char*)part + align_up(rp * (size_t)n * 4 * 16, 256);
-    launch_split_act(x, rows, k_dim, a, s);
-    launch_pack_weights(wseg1(w, n), n, k_dim, wpk, s);
-    GemmPlan plan = gemm_mfma_plan(rows, n, k_dim, 0);
-    launch_gemm_mfma(a, wpk, part, n, rp * n, rows, n, k_dim, plan, s);
-    launch_reduce_partials(Partial{part, plan.S, rp * (size_t)n, n}, y, rows, s);
+    gemm_in_workspace(x, w, y, rows, n, k_dim, workspace, s);
   } else {
     return FIRP_EINVAL;
   }
   return hipGetLastError() == hipSuccess ? FIRP_OK : FIRP_EDEVICE;
+}
+
+// ---- the projection entry that allocates nothing -------------------------------------------------
+// Its scratch (operand planes, split-K partial sums, the fragment-major copy of w) is a fixed
+// array in device memory that every GPU the library runs on holds until the process ends.  In
+// host code the array's name is only a handle: its device address is looked up once per device
+// and that pointer is what the kernels get.
+#define FIRP_STATIC_SCRATCH_BYTES ((size_t)32 << 20)
+#define FIRP_MAX_DEVICES 64
+static __device__ __align__(256) unsigned char scratch[FIRP_STATIC_SCRATCH_BYTES];
+static void* g_scratch_ptr[FIRP_MAX_DEVICES];
+
+size_t firp_gemm_static_capacity(void) { return FIRP_STATIC_SCRATCH_BYTES; }
+
+firp_status firp_debug_gemm_static(const float* x, const void* w, float* y, int32_t rows, int32_t n, int32_t k_dim,
+                                   void* hip_stream) {
+  auto bad = [&](firp_status code, const std::string& m) {
+    g_init_error = m;
+    return code;
+  };
+  if (!x || !w || !y || rows < 1 || n < 1 || k_dim < 1) return bad(FIRP_EINVAL, "firp_debug_gemm_static: NULL pointer or non-positive size");
+  if (!gemm_mfma_supported(rows, n, k_dim)) return bad(FIRP_EINVAL, "firp_debug_gemm_static: n must be a multiple of 4 and K a multiple of 8");
+  const size_t need = firp_gemm_workspace_bytes(rows, n, k_dim);
+  if (need > FIRP_STATIC_SCRATCH_BYTES) {
+    char buf[256];
+    snprintf(buf, sizeof buf, "firp_debug_gemm_static: %d x %d x %d needs %zu bytes of scratch, the fixed buffer holds %zu",
+             rows, n, k_dim, need, (size_t)FIRP_STATIC_SCRATCH_BYTES);
+    return bad(FIRP_ECAPACITY, buf);
+  }
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= FIRP_MAX_DEVICES) return bad(FIRP_EDEVICE, "firp_debug_gemm_static: no current device");
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !p) return bad(FIRP_EDEVICE, std::string("firp_debug_gemm_static: hipGetSymbolAddress failed: ") + hipGetErrorString(e));
+    g_scratch_ptr[dev] = p;
+  }
+  gemm_in_workspace(x, w, y, rows, n, k_dim, g_scratch_ptr[dev], (hipStream_t)hip_stream);
+  return hipGetLastError() == hipSuccess ? FIRP_OK : bad(FIRP_EDEVICE, "firp_debug_gemm_static: kernel launch failed");
 }
 
 firp_status firp_debug_stream_read(const void* src, size_t bytes, void* sink, void* hip_stream) {
