@@ -19,10 +19,26 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E bandwidth
-# HBM bytes moved per algorithmic weight byte by the projection kernel at the 13B shapes,
-# weighted by each shape's share of a step: (FETCH_SIZE + WRITE_SIZE) / weights from the
-# rocprofv3 --pmc runs summarised in profiles/k_gemm_mfma_13b_shapes_hbm_traffic.md
-GEMM_TRAFFIC_RATIO_13B = 1.171
+PROFILES = os.path.join(ROOT, "profiles")
+
+
+def profile_figures():
+    """Figures of the committed rocprofv3 summaries that the bench line quotes: HBM bytes moved
+    per weight byte by the projection kernel at the 13B shapes ((FETCH_SIZE + WRITE_SIZE) / weights,
+    weighted by each shape's share of a step) and the kernel-trace mean duration of a decode-step
+    launch of that kernel.  None where a summary or its line is missing."""
+    import re
+    out = {"traffic_ratio": None, "trace_avg_launch_us": None}
+    for fname, key, pat in (("k_gemm_mfma_13b_shapes_hbm_traffic.md", "traffic_ratio", r"traffic_ratio_13b_step\s*=\s*([0-9.]+)"),
+                            ("firp_step_13b_kernel_stats.md", "trace_avg_launch_us", r"decode_launch_trace_mean_us\s*=\s*([0-9.]+)")):
+        try:
+            with open(os.path.join(PROFILES, fname)) as f:
+                m = re.search(pat, f.read())
+            if m:
+                out[key] = float(m.group(1))
+        except OSError:
+            pass
+    return out
 
 
 def algorithmic_bytes(cfg, n_nodes: int, t_hi: int, ctx: int, batch: int = 1) -> float:
@@ -38,44 +54,29 @@ def algorithmic_bytes(cfg, n_nodes: int, t_hi: int, ctx: int, batch: int = 1) ->
     return float(weights + batch * (kv_sweep + step_rows))
 
 
-def cpu_baseline(cfg, weights_gpu, tree, prompt, budget_note: str):
-    """Time the CPU oracle, as it stands, on a bounded sample of the same workload: the same
-    widths, prompt and tree with only the first 2 and the first 4 of the layers; the per-layer
-    cost from the difference is extrapolated to the full depth."""
-    # (about 20 s of CPU work including the two prefills)
+def cpu_baseline(cfg, weights_gpu, tree, prompt, n_steps: int = 3):
+    """Time the CPU oracle, as it stands, on the same workload at full depth: its prefill of the
+    whole prompt (not timed), then `n_steps` decoding steps with the benchmark's tree."""
     import torch
-    from paper_2410_20488_amd import synth
-    from tests.helpers import make_oracle
+    from oracle.firp_oracle import FirpOracle
 
-    def sample(n_layers):
-        sub = synth.scaled_config(cfg, n_layers, n_layers // 2)
-        w = {}
-        for k, v in weights_gpu.items():
-            if v is None:
-                w[k] = None
-            elif isinstance(v, list):
-                keep = v if k.startswith("proj") else v[:n_layers]
-                w[k] = [t.cpu() for t in keep]
-            else:
-                w[k] = v.cpu()
-        o = make_oracle(sub, w)
-        o.prefill(prompt)
-        args = dict(parent=list(tree.parent), rank=list(tree.rank), anchor=list(tree.anchor))
-        t0 = time.perf_counter()
-        for _ in range(3):
-            o.step(**args)
-        return (time.perf_counter() - t0) / 3.0
-
-    la, lb = 4, 8
-    t2 = sample(la)
-    t4 = sample(lb)
-    per_layer = max((t4 - t2) / float(lb - la), 0.0)
-    full = t2 + per_layer * (cfg.n_layers - la)
-    return {"value": round(full * 1e3, 1), "unit": "ms/step", "cores": torch.get_num_threads(), "kind": "oracle",
-            "sample": f"fp32 oracle: 3 steps each at the full widths, prompt and tree with {la} and with {lb} of the "
-                      f"{cfg.n_layers} layers ({t2:.2f} s and {t4:.2f} s per step); per-layer cost extrapolated to "
-                      f"full depth"
-                      + budget_note}
+    w = {}
+    for k, v in weights_gpu.items():
+        w[k] = None if v is None else ([t.cpu() for t in v] if isinstance(v, (list, tuple)) else v.cpu())
+    o = FirpOracle(n_layers=cfg.n_layers, d_model=cfg.d_model, n_q_heads=cfg.n_q_heads, n_kv_heads=cfg.n_kv_heads,
+                   head_dim=cfg.head_dim, d_ffn=cfg.d_ffn, vocab=cfg.vocab, rms_eps=cfg.rms_eps,
+                   rope_base=cfg.rope_base, weights=w, firp_layer=cfg.firp_layer, k=cfg.k, b_max=8,
+                   dtype=torch.float32, kv_round_bf16=cfg.dtype == "bf16", firp_layers=cfg.firp_layers)
+    t_pre = time.perf_counter()
+    o.prefill(prompt)
+    t0 = time.perf_counter()
+    args = dict(parent=list(tree.parent), rank=list(tree.rank), anchor=list(tree.anchor))
+    for _ in range(n_steps):
+        o.step(**args)
+    per_step = (time.perf_counter() - t0) / n_steps
+    return {"value": round(per_step * 1e3, 1), "unit": "ms/step", "cores": torch.get_num_threads(), "kind": "oracle",
+            "sample": f"fp32 oracle at full depth ({cfg.n_layers} layers): {n_steps} decoding steps of the same tree "
+                      f"after its own prefill of the {len(prompt)}-token prompt ({t0 - t_pre:.1f} s, not timed)"}
 
 
 def main() -> int:
@@ -104,7 +105,7 @@ def main() -> int:
 
     import torch
     from paper_2410_20488_amd import synth
-    from tests.gpu_common import make_engine
+    from paper_2410_20488_amd import binding
 
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
@@ -131,7 +132,7 @@ def main() -> int:
     n_anchor = sum(tree.anchor)
     t_hi = tree.n_nodes + cfg.k * n_anchor
     total_steps = args.warmup + args.steps + 16
-    eng = make_engine(cfg, weights, max_ctx=prompt_len + (cfg.k + 1) * (total_steps + 2) + 8,
+    eng = binding.engine_for_config(cfg, weights, max_ctx=prompt_len + (cfg.k + 1) * (total_steps + 2) + 8,
                       max_batch=args.batch, max_nodes=tree.n_nodes, max_rows=max(128, t_hi), b_max=8)
     prompts = [synth.prompt_tokens(cfg.seed, prompt_len, cfg.vocab, stream=b).tolist() for b in range(args.batch)]
     prompt = prompts[0]
@@ -161,11 +162,15 @@ def main() -> int:
     for _ in range(16):
         eng.step(*targs)
     launches, gemm_ms, gemm_bytes = eng.gemm_timing()
+    bracket_us = eng.event_bracket_us()      # what an empty pair of events on the same stream reads
     eng.set_option("time_gemm", 0)
-    gemm_gbs = gemm_bytes / (gemm_ms * 1e-3) / 1e9 if gemm_ms > 0 else 0.0
+    event_us = gemm_ms * 1e3 / max(launches, 1)
+    kernel_us = max(event_us - bracket_us, 1e-3)
+    gemm_gbs = gemm_bytes / max(launches, 1) / (kernel_us * 1e-6) / 1e9 if gemm_ms > 0 else 0.0
+    prof = profile_figures() if args.config == "13b" and args.anchors == "root" and args.batch == 1 else \
+        {"traffic_ratio": None, "trace_avg_launch_us": None}
 
     # the rate a kernel that only reads can reach on this chip (8 GiB, far beyond every cache)
-    from paper_2410_20488_amd import binding
     ceiling_gbs = binding.stream_read_gbps()
 
     step_bytes = algorithmic_bytes(cfg, tree.n_nodes, t_hi, (ctx_first + ctx_last) // 2, args.batch)
@@ -189,16 +194,23 @@ def main() -> int:
         "setup_s": round(setup_s, 1),
         "roofline": {"bound": "hbm", "kernel": "k_gemm_mfma", "achieved": round(gemm_gbs, 1), "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": round(gemm_gbs / HBM_PEAK_GBS, 4),
-                     "traffic": (round(GEMM_TRAFFIC_RATIO_13B * gemm_bytes / max(launches, 1), 0)
-                                 if args.config == "13b" else None),
+                     "traffic": (round(prof["traffic_ratio"] * gemm_bytes / max(launches, 1), 0)
+                                 if prof["traffic_ratio"] else None),
                      "launches_timed": launches,
-                     "avg_launch_us": round(gemm_ms * 1e3 / max(launches, 1), 2),
+                     "avg_launch_us": round(kernel_us, 2),
+                     "avg_launch_us_is": "HIP-event bracket around every launch on the library's stream minus the "
+                                         "reading of an empty bracket, both measured in this run",
+                     "event_bracket_avg_us": round(event_us, 2), "empty_bracket_us": round(bracket_us, 2),
+                     "frac_by_raw_event_brackets": round(gemm_bytes / max(gemm_ms, 1e-9) / 1e6 / HBM_PEAK_GBS, 4),
+                     "profile_trace_avg_launch_us": prof["trace_avg_launch_us"],
+                     "traffic_is": "algorithmic bytes per launch x the (FETCH_SIZE + WRITE_SIZE) / weight-bytes ratio "
+                                   "of profiles/k_gemm_mfma_13b_shapes_hbm_traffic.md",
                      "algorithmic_MB_per_launch": round(gemm_bytes / max(launches, 1) / 1e6, 2),
-                     "share_of_step_time": round(gemm_ms / 16 / ms_per_step, 3)},
+                     "share_of_step_time": round(kernel_us * 1e-3 * launches / 16 / ms_per_step, 3)},
     }
     if not args.no_cpu_baseline and args.batch == 1:
         del eng
-        out["cpu_baseline"] = cpu_baseline(cfg, weights, tree, prompt, "")
+        out["cpu_baseline"] = cpu_baseline(cfg, weights, tree, prompt)
     print(json.dumps(out))
     return 0
 

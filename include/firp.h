@@ -234,6 +234,11 @@ firp_status firp_set_option(firp_ctx *ctx, const char *name, int32_t value);
 firp_status firp_get_gemm_timing(const firp_ctx *ctx, int64_t *launches, double *total_ms,
                                  double *weight_bytes);
 
+/* What a pair of HIP events with nothing between them reads on the library's stream (mean over
+ * the steps since "time_gemm" was set, one empty bracket per step; 0 before any): the share of
+ * a bracketed launch's reading that is not the kernel. */
+firp_status firp_get_event_overhead(const firp_ctx *ctx, double *bracket_ms);
+
 /* Standalone entry to the projection kernel for per-kernel parity and bandwidth tests:
  * y[R, n] (DEVICE fp32) = x[R, K] (DEVICE fp32) . w[n, K]^T (DEVICE, `dtype`), on `hip_stream`,
  * using `workspace` (DEVICE, >= firp_gemm_workspace_bytes(R, n, K)) for operand planes,

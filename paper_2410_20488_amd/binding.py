@@ -83,6 +83,7 @@ def load_library() -> C.CDLL:
         "firp_debug_read_cache": (C.c_int, [vp, C.c_int32, C.c_int32, C.POINTER(C.c_float), C.POINTER(C.c_float)]),
         "firp_set_option": (C.c_int, [vp, C.c_char_p, C.c_int32]),
         "firp_get_gemm_timing": (C.c_int, [vp, C.POINTER(C.c_int64), C.POINTER(C.c_double), C.POINTER(C.c_double)]),
+        "firp_get_event_overhead": (C.c_int, [vp, C.POINTER(C.c_double)]),
         "firp_gemm_workspace_bytes": (C.c_size_t, [C.c_int32, C.c_int32, C.c_int32]),
         "firp_debug_stream_read": (C.c_int32, [C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]),
         "firp_debug_gemm_plan": (C.c_int32, [C.c_int32, C.c_int32, C.c_int32] + [C.POINTER(C.c_int32)] * 5),
@@ -102,7 +103,7 @@ EXPORTED = ["firp_workspace_bytes", "firp_init", "firp_init_layers", "firp_build
             "firp_last_error", "firp_step_with_candidates", "firp_check_tree", "firp_debug_last_logits", "firp_debug_last_path",
             "firp_get_drafts", "firp_get_ctx_len", "firp_debug_read_cache", "firp_set_option", "firp_get_gemm_timing",
             "firp_gemm_workspace_bytes", "firp_debug_gemm", "firp_debug_gemm_plan", "firp_debug_stream_read",
-            "firp_gemm_static_capacity", "firp_debug_gemm_static"]
+            "firp_gemm_static_capacity", "firp_debug_gemm_static", "firp_get_event_overhead"]
 
 
 def _i32(a) -> np.ndarray:
@@ -301,6 +302,12 @@ class Engine:
         self._check(self.lib.firp_get_gemm_timing(self.ctx, C.byref(n), C.byref(ms), C.byref(by)))
         return n.value, ms.value, by.value
 
+    def event_bracket_us(self) -> float:
+        """Mean reading (microseconds) of an empty pair of events on the library's stream."""
+        ms = C.c_double(0)
+        self._check(self.lib.firp_get_event_overhead(self.ctx, C.byref(ms)))
+        return ms.value * 1e3
+
     def read_cache(self, seq: int, layer: int):
         n = self.ctx_len()[seq]
         shape = (n, self.desc.n_kv_heads, self.desc.head_dim)
@@ -308,6 +315,18 @@ class Engine:
         v = np.zeros(shape, dtype=np.float32)
         self._check(self.lib.firp_debug_read_cache(self.ctx, seq, layer, _p(k, C.c_float), _p(v, C.c_float)))
         return k, v
+
+
+def engine_for_config(cfg, weights, *, max_ctx: int, max_batch: int = 1, max_nodes: int = 64, max_rows: int = 128,
+                      b_max: int = 8, gemm: Optional[int] = None) -> Engine:
+    """An Engine for a synthetic model configuration (synth.ModelConfig) and its weight dict."""
+    e = Engine(n_layers=cfg.n_layers, d_model=cfg.d_model, n_q_heads=cfg.n_q_heads, n_kv_heads=cfg.n_kv_heads,
+               head_dim=cfg.head_dim, d_ffn=cfg.d_ffn, vocab=cfg.vocab, rms_eps=cfg.rms_eps, rope_base=cfg.rope_base,
+               dtype=cfg.dtype, weights=weights, firp_layer=cfg.firp_layer, k=cfg.k, max_ctx=max_ctx,
+               max_batch=max_batch, max_nodes=max_nodes, max_rows=max_rows, b_max=b_max, firp_layers=cfg.firp_layers)
+    if gemm is not None:
+        e.set_option("gemm", gemm)
+    return e
 
 
 def debug_gemm(x: torch.Tensor, w: torch.Tensor, kind: int) -> torch.Tensor:

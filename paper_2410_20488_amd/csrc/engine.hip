@@ -101,6 +101,9 @@ struct firp_ctx {
   size_t ev_used = 0;
   double gemm_ms = 0.0, gemm_bytes = 0.0;
   long gemm_launches = 0;
+  hipEvent_t ev_empty[2] = {nullptr, nullptr};   // a bracket with nothing in it, once per timed step
+  double empty_ms = 0.0;
+  long empty_n = 0;
   int* h_result = nullptr;  // pinned when a device is present
   bool h_result_pinned = true;
   std::string err;
@@ -601,6 +604,11 @@ firp_status run_step(firp_ctx* c, const firp_tree* tree, const int32_t* node_tok
     inj = c->injected;
   }
   launch_fill_tokens(c->st, tree_tab(c, N, P), B, inj, s);
+  const bool empty_bracket = c->time_gemm && c->ev_empty[0];
+  if (empty_bracket) {
+    (void)hipEventRecord(c->ev_empty[0], s);
+    (void)hipEventRecord(c->ev_empty[1], s);
+  }
   st = forward(c, B, N, n_anchor, true, ctx_max, 0, 0, c->k);
   if (st != FIRP_OK) return st;
   launch_verify_select(c->st, tree_tab(c, N, P), B, s);
@@ -612,6 +620,13 @@ firp_status run_step(firp_ctx* c, const firp_tree* tree, const int32_t* node_tok
     if (hipEventElapsedTime(&ms, c->ev[i], c->ev[i + 1]) == hipSuccess) c->gemm_ms += ms;
   }
   c->ev_used = 0;
+  if (empty_bracket) {
+    float ms = 0.f;
+    if (hipEventElapsedTime(&ms, c->ev_empty[0], c->ev_empty[1]) == hipSuccess) {
+      c->empty_ms += ms;
+      c->empty_n += 1;
+    }
+  }
   for (int b = 0; b < B; ++b) {
     const int* r = c->h_result + b * FIRP_RESULT_STRIDE;
     n_accepted[b] = r[0];
@@ -739,6 +754,8 @@ firp_status firp_reset(firp_ctx* c) {
 void firp_destroy(firp_ctx* c) {
   if (!c) return;
   for (auto& e : c->ev) (void)hipEventDestroy(e);
+  for (auto& e : c->ev_empty)
+    if (e) (void)hipEventDestroy(e);
   if (c->h_result) {
     if (c->h_result_pinned)
       (void)hipHostFree(c->h_result);
@@ -1026,9 +1043,14 @@ firp_status firp_set_option(firp_ctx* c, const char* name, int32_t value) {
           return c->fail(FIRP_EDEVICE, "hipEventCreate failed");
         }
     }
+    if (value && !c->ev_empty[0])
+      for (auto& e : c->ev_empty)
+        if (hipEventCreate(&e) != hipSuccess) return c->fail(FIRP_EDEVICE, "hipEventCreate failed");
     c->time_gemm = value != 0;
     c->gemm_ms = c->gemm_bytes = 0.0;
     c->gemm_launches = 0;
+    c->empty_ms = 0.0;
+    c->empty_n = 0;
     c->ev_used = 0;
     return FIRP_OK;
   }
@@ -1040,6 +1062,12 @@ firp_status firp_get_gemm_timing(const firp_ctx* c, int64_t* launches, double* t
   if (launches) *launches = c->gemm_launches;
   if (total_ms) *total_ms = c->gemm_ms;
   if (weight_bytes) *weight_bytes = c->gemm_bytes;
+  return FIRP_OK;
+}
+
+firp_status firp_get_event_overhead(const firp_ctx* c, double* bracket_ms) {
+  if (!c || !bracket_ms) return FIRP_EINVAL;
+  *bracket_ms = c->empty_n > 0 ? c->empty_ms / (double)c->empty_n : 0.0;
   return FIRP_OK;
 }
 

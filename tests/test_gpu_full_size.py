@@ -26,10 +26,13 @@ def test_full_depth_model_matches_oracle(name, prompt_len, n_steps, layers, prog
     tree = synth.workload_tree(name)
     rep, eng, orc = run_lockstep(cfg, w, tree, prompt_len=prompt_len, n_steps=n_steps, tol=2e-2,
                                  progress=progress, max_rows=128, oracle_dtype=torch.float32)
-    progress(f"{name}: max logit err {rep.max_logit_err:.3e}, ties {rep.tie_ambiguous}, "
-             f"accepted histogram {rep.accepted_hist}")
+    progress(f"{name}: max logit err {rep.max_logit_err:.3e}, near-ties: tokens {rep.tie_tokens}, draft lists "
+             f"{rep.tie_drafts}, accepted histogram {rep.accepted_hist}")
+    print(f"{name}: max logit err {rep.max_logit_err:.3e}, near-ties: tokens {rep.tie_tokens}, drafts {rep.tie_drafts}")
     assert rep.steps == n_steps
-    assert rep.tie_ambiguous <= n_steps        # near-ties are rare, not the rule
+    # a committed token may differ only at a near-tie (two best logits within 2e-2 of a standard
+    # deviation): rare; the order inside a draft list (24 adjacent pairs per step) ties more often
+    assert rep.tie_tokens <= 1 and rep.tie_drafts <= n_steps
 
 
 def test_34b_widths_batch_of_four(progress):
@@ -46,9 +49,49 @@ def test_34b_widths_batch_of_four(progress):
                                         progress=progress, oracle_dtype=torch.float32)
     progress(f"34b widths: max logit err {rep.max_logit_err:.3e}, ties {rep.tie_ambiguous}, "
              f"accepted histogram {rep.accepted_hist}")
+    print(f"34b widths: max logit err {rep.max_logit_err:.3e}, near-ties: tokens {rep.tie_tokens}, drafts {rep.tie_drafts}")
     assert rep.steps == 4
-    assert rep.tie_ambiguous <= 8               # of 16 (sequence, step) pairs
+    assert rep.tie_tokens <= 2 and rep.tie_drafts <= 8      # of 16 (sequence, step) pairs
     assert sum(rep.accepted_hist[2:]) > 0        # planted continuations were accepted
+
+
+def test_7b_full_depth_8k_context(progress):
+    """The long-context workload at its own size: the 7B shape at full depth (32 layers), a prompt
+    of 8192 tokens, the 64-node tree: cache offsets beyond 8k, the attention kernel's split count
+    and chunk length at that length, position ids in the thousands, in the launch configuration
+    bench.py times (`--config 7b --tree 13b --prompt 8192`).  The oracle (fp32) needs a few
+    minutes for its plain causal prefill of 8191 tokens; two steps follow in lockstep."""
+    dev = torch.device("cuda:0")
+    cfg = synth.CONFIGS["7b"]
+    progress("7b 8k: generating weights")
+    w = synth.make_weights(cfg, dev)
+    tree = synth.workload_tree("13b")
+    rep, eng, orc = run_lockstep(cfg, w, tree, prompt_len=8192, n_steps=2, tol=2e-2, progress=progress,
+                                 max_rows=128, oracle_dtype=torch.float32, with_injection=False)
+    progress(f"7b 8k: max logit err {rep.max_logit_err:.3e}, near-ties: tokens {rep.tie_tokens}, draft lists {rep.tie_drafts}")
+    print(f"7b 8k: max logit err {rep.max_logit_err:.3e}, near-ties: tokens {rep.tie_tokens}, drafts {rep.tie_drafts}")
+    assert rep.steps == 2 and eng.ctx_len()[0] == orc.p0 >= 8192 + 1
+    assert rep.tie_tokens <= 1 and rep.tie_drafts <= 3
+
+
+def test_34b_widths_batch_of_four_2k_prompts(progress):
+    """The 34B-shaped workload's own batch and prompt sizes: four sequences with prompts of about
+    2048 tokens (unequal: 2048, 2011, 1987, 2040), 4 x 67 = 268 rows in every projection, grouped
+    key/value heads, at the depth the oracle finishes in about a minute: 6 of the 48 layers, the
+    maps at layer 3.  Three steps in lockstep with one oracle per sequence."""
+    from tests.gpu_common import run_lockstep_batch
+    dev = torch.device("cuda:0")
+    cfg = synth.scaled_config(synth.CONFIGS["34b"], 6, 3)
+    progress("34b 2k: generating weights")
+    w = synth.make_weights(cfg, dev)
+    tree = synth.workload_tree("34b")
+    rep, eng, orcs = run_lockstep_batch(cfg, w, tree, prompt_lens=[2048, 2011, 1987, 2040], n_steps=3, tol=2e-2,
+                                        progress=progress, oracle_dtype=torch.float32)
+    progress(f"34b 2k: max logit err {rep.max_logit_err:.3e}, near-ties: tokens {rep.tie_tokens}, draft lists {rep.tie_drafts}")
+    print(f"34b 2k: max logit err {rep.max_logit_err:.3e}, near-ties: tokens {rep.tie_tokens}, drafts {rep.tie_drafts}")
+    assert rep.steps == 3
+    assert rep.tie_tokens <= 2 and rep.tie_drafts <= 6      # of 12 (sequence, step) pairs
+    assert sum(rep.accepted_hist[2:]) > 0
 
 
 def test_13b_full_depth_decoding_is_lossless(progress):
