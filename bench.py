@@ -79,6 +79,71 @@ def cpu_baseline(cfg, weights_gpu, tree, prompt, n_steps: int = 3):
                       f"after its own prefill of the {len(prompt)}-token prompt ({t0 - t_pre:.1f} s, not timed)"}
 
 
+def accept_pattern_run(eng, cfg, tree, prompts, warmup: int, steps: int):
+    """Decode with planted candidates: step i of the rotation carries the true greedy continuation
+    for i mod (k+1) levels along the chain of last children (every other candidate is wrong), so
+    that many candidates are accepted.  The true continuation comes from plain greedy decoding
+    (root-only steps) on the same engine first.  A step whose path ends on a node without pseudo
+    rows leaves no drafts: the next call of firp_step then runs the root-only sub-tree by itself
+    and counts as a step of its own."""
+    import torch
+    from paper_2410_20488_amd import synth
+    assert len(prompts) == 1, "--accept-pattern runs one sequence"
+    prompt, N, k = prompts[0], tree.n_nodes, cfg.k
+    targs = (list(tree.parent), list(tree.rank), list(tree.anchor))
+    need = (warmup + steps + 2) * (k + 1) + 8
+    g = eng.prefill([prompt])
+    while len(g) < need:
+        g += eng.step([-1], [0], [0])[0]
+    emitted = eng.prefill([prompt])
+    kids = [[c for c in range(N) if tree.parent[c] == v] for v in range(N)]
+    state = {"i": 0, "mismatch": 0, "full": 0, "root_only": 0, "planted": 0}
+
+    def one_step():
+        pos = len(emitted)
+        valid = eng.drafts_valid_host()[0]
+        if not valid:                                     # no drafts: the library runs the root alone
+            got = eng.step(*targs)[0]
+            state["root_only"] += 1
+        else:
+            plant = state["i"] % (k + 1)
+            state["i"] += 1
+            truth = g[pos:pos + k + 1]
+            cand = [(t + 7) % cfg.vocab if t in truth else t
+                    for t in synth.prompt_tokens(state["i"], N, cfg.vocab, stream=9).tolist()]
+            v = 0
+            for lvl in range(plant):
+                if not kids[v]:
+                    break
+                v = kids[v][-1]
+                cand[v] = g[pos + lvl]
+            got = eng.step_with_candidates(*targs, [cand])[0]
+            state["full"] += 1
+            state["planted"] += plant
+        if got != g[pos:pos + len(got)]:
+            state["mismatch"] += 1                        # a near-tie between the two launch shapes
+        emitted.extend(got)
+        return len(got)
+
+    for _ in range(warmup):
+        one_step()
+    state.update(full=0, root_only=0, planted=0)
+    ctx_first = eng.ctx_len()[0]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    stamps, tokens = [t0], 0
+    for _ in range(steps):
+        tokens += one_step()
+        stamps.append(time.perf_counter())
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    per = sorted((b - a) * 1e3 for a, b in zip(stamps, stamps[1:]))
+    return {"ms_per_step": (t1 - t0) * 1e3 / steps, "per_step_ms": per, "tokens": tokens, "ctx_first": ctx_first,
+            "full_tree_steps": state["full"], "root_only_steps": state["root_only"],
+            "ms_per_token": round((t1 - t0) * 1e3 / max(tokens, 1), 4),
+            "continuation_mismatches": state["mismatch"], "topologies_uploaded": eng.stat("topo_uploads")}
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -93,6 +158,11 @@ def main() -> int:
     ap.add_argument("--firp-layers", default="",
                     help="comma-separated prediction layer per step (e.g. 25,30,35: the paper's 13B setting); "
                          "default: the benchmark configuration's single layer")
+    ap.add_argument("--accept-pattern", action="store_true",
+                    help="instead of the library's own (untrained, never accepted) drafts, plant the true greedy "
+                         "continuation so that 0, 1, .. k candidates are accepted in rotation, as trained maps would "
+                         "have it: with the root as the only anchor every step that accepts a candidate is followed "
+                         "by a root-only step (no drafts)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a plain 1 GiB device copy three times (reference for scaling the "
@@ -131,7 +201,7 @@ def main() -> int:
     torch.cuda.synchronize()
     n_anchor = sum(tree.anchor)
     t_hi = tree.n_nodes + cfg.k * n_anchor
-    total_steps = args.warmup + args.steps + 16
+    total_steps = args.warmup + args.steps + 16 + (2 * (args.warmup + args.steps) if args.accept_pattern else 0)
     eng = binding.engine_for_config(cfg, weights, max_ctx=prompt_len + (cfg.k + 1) * (total_steps + 2) + 8,
                       max_batch=args.batch, max_nodes=tree.n_nodes, max_rows=max(128, t_hi), b_max=8)
     prompts = [synth.prompt_tokens(cfg.seed, prompt_len, cfg.vocab, stream=b).tolist() for b in range(args.batch)]
@@ -139,22 +209,28 @@ def main() -> int:
     eng.prefill(prompts)
     setup_s = time.time() - t_start
     targs = (list(tree.parent), list(tree.rank), list(tree.anchor))
-    for _ in range(args.warmup):
-        eng.step(*targs)
-    ctx_first = eng.ctx_len()[0]
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    tokens = 0
-    stamps = [t0]   # every step ends with its own host synchronisation (it returns the tokens)
-    for _ in range(args.steps):
-        tokens += sum(len(t) for t in eng.step(*targs))
-        stamps.append(time.perf_counter())
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    per_step = sorted((b - a) * 1e3 for a, b in zip(stamps, stamps[1:]))
+    pattern = None
+    if args.accept_pattern:
+        pattern = accept_pattern_run(eng, cfg, tree, prompts, args.warmup, args.steps)
+        ms_per_step, per_step, tokens = pattern["ms_per_step"], pattern["per_step_ms"], pattern["tokens"]
+        ctx_first, ctx_last = pattern["ctx_first"], eng.ctx_len()[0]
+    else:
+        for _ in range(args.warmup):
+            eng.step(*targs)
+        ctx_first = eng.ctx_len()[0]
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        tokens = 0
+        stamps = [t0]   # every step ends with its own host synchronisation (it returns the tokens)
+        for _ in range(args.steps):
+            tokens += sum(len(t) for t in eng.step(*targs))
+            stamps.append(time.perf_counter())
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        per_step = sorted((b - a) * 1e3 for a, b in zip(stamps, stamps[1:]))
+        ctx_last = eng.ctx_len()[0]
+        ms_per_step = (t1 - t0) * 1e3 / args.steps
     pct = lambda q: per_step[min(len(per_step) - 1, int(q * len(per_step)))]
-    ctx_last = eng.ctx_len()[0]
-    ms_per_step = (t1 - t0) * 1e3 / args.steps
 
     # roofline of the dominant kernel (the weight-streaming projection): HIP events on the
     # library's stream around every launch, over 16 further steps
@@ -190,7 +266,7 @@ def main() -> int:
         "step_frac_of_hbm_peak": round(step_gbs / HBM_PEAK_GBS, 4),
         "stream_read_ceiling_GBps": round(ceiling_gbs, 1),
         "step_frac_of_stream_read_ceiling": round(step_gbs / ceiling_gbs, 4),
-        "tokens_per_step": round(tokens / args.steps, 3),
+        "tokens_per_step": round(tokens / args.steps / args.batch, 3),
         "setup_s": round(setup_s, 1),
         "roofline": {"bound": "hbm", "kernel": "k_gemm_mfma", "achieved": round(gemm_gbs, 1), "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": round(gemm_gbs / HBM_PEAK_GBS, 4),
@@ -208,6 +284,8 @@ def main() -> int:
                      "algorithmic_MB_per_launch": round(gemm_bytes / max(launches, 1) / 1e6, 2),
                      "share_of_step_time": round(kernel_us * 1e-3 * launches / 16 / ms_per_step, 3)},
     }
+    if pattern is not None:
+        out["accept_pattern"] = {k: v for k, v in pattern.items() if k not in ("per_step_ms",)}
     if not args.no_cpu_baseline and args.batch == 1:
         del eng
         out["cpu_baseline"] = cpu_baseline(cfg, weights, tree, prompt)

@@ -206,13 +206,17 @@ firp_status firp_build_tree(const float *accept, int32_t k, int32_t b, int32_t n
 
 /* Logits of the last step, HOST [batch][T_hi][V] fp32, rows in step order: the tree nodes, then
  * pseudo row 1 of every anchor (ascending node id), then pseudo row 2 of every anchor, ...
- * n_rows receives T_hi. */
+ * n_rows receives T_hi.  A decoding step writes its logits to memory only with the option
+ * "keep_logits" set (it needs no more than the greedy token of every node and the top-b ids of
+ * every pseudo row); without it this call returns FIRP_ESTATE. */
 firp_status firp_debug_last_logits(firp_ctx *ctx, float *logits, int32_t *n_rows);
 
 /* Node ids of the last accepted path, HOST [batch][FIRP_MAX_K + 1]. */
 firp_status firp_debug_last_path(firp_ctx *ctx, int32_t *path_nodes);
 
-/* Current drafts, HOST [batch][k][b_max]; valid HOST [batch] (0 = next step is root-only). */
+/* Current drafts, HOST [batch][k][b_max]; valid HOST [batch] (0 = next step is root-only).
+ * drafts may be NULL: then only the flags are returned, from the host's mirror, with no device
+ * work and no synchronisation. */
 firp_status firp_get_drafts(const firp_ctx *ctx, int32_t *drafts, int32_t *valid);
 
 /* Committed cache length of each sequence, HOST [batch]. */
@@ -225,7 +229,7 @@ firp_status firp_debug_read_cache(firp_ctx *ctx, int32_t seq, int32_t layer, flo
 
 /* Behaviour switches for tests and measurements.  name = "gemm" value 0 (plain tiled kernel)
  * or 1 (MFMA weight-streaming kernel, bf16 models only; the default for them); "time_gemm" 0/1
- * (see firp_get_gemm_timing).  Returns FIRP_EINVAL for an unknown name or value. */
+ * (see firp_get_gemm_timing); "keep_logits" 0/1 (default 0: see firp_debug_last_logits).  Returns FIRP_EINVAL for an unknown name or value. */
 firp_status firp_set_option(firp_ctx *ctx, const char *name, int32_t value);
 
 /* With option "time_gemm" = 1 every launch of the MFMA projection kernel inside firp_step is
@@ -233,6 +237,12 @@ firp_status firp_set_option(firp_ctx *ctx, const char *name, int32_t value);
  * was set: kernel launches, their summed duration, and the weight bytes they streamed. */
 firp_status firp_get_gemm_timing(const firp_ctx *ctx, int64_t *launches, double *total_ms,
                                  double *weight_bytes);
+
+/* Counters of the context since firp_init, by name: "topo_uploads" = tree topologies whose
+ * tables were uploaded to the device (the last few topologies stay resident: switching
+ * between them, e.g. between a tree and its root-only sub-tree, uploads nothing).
+ * FIRP_EINVAL for an unknown name. */
+firp_status firp_get_stat(const firp_ctx *ctx, const char *name, int64_t *value);
 
 /* What a pair of HIP events with nothing between them reads on the library's stream (mean over
  * the steps since "time_gemm" was set, one empty bracket per step; 0 before any): the share of

@@ -84,6 +84,7 @@ def load_library() -> C.CDLL:
         "firp_set_option": (C.c_int, [vp, C.c_char_p, C.c_int32]),
         "firp_get_gemm_timing": (C.c_int, [vp, C.POINTER(C.c_int64), C.POINTER(C.c_double), C.POINTER(C.c_double)]),
         "firp_get_event_overhead": (C.c_int, [vp, C.POINTER(C.c_double)]),
+        "firp_get_stat": (C.c_int, [vp, C.c_char_p, C.POINTER(C.c_int64)]),
         "firp_gemm_workspace_bytes": (C.c_size_t, [C.c_int32, C.c_int32, C.c_int32]),
         "firp_debug_stream_read": (C.c_int32, [C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]),
         "firp_debug_gemm_plan": (C.c_int32, [C.c_int32, C.c_int32, C.c_int32] + [C.POINTER(C.c_int32)] * 5),
@@ -103,7 +104,7 @@ EXPORTED = ["firp_workspace_bytes", "firp_init", "firp_init_layers", "firp_build
             "firp_last_error", "firp_step_with_candidates", "firp_check_tree", "firp_debug_last_logits", "firp_debug_last_path",
             "firp_get_drafts", "firp_get_ctx_len", "firp_debug_read_cache", "firp_set_option", "firp_get_gemm_timing",
             "firp_gemm_workspace_bytes", "firp_debug_gemm", "firp_debug_gemm_plan", "firp_debug_stream_read",
-            "firp_gemm_static_capacity", "firp_debug_gemm_static", "firp_get_event_overhead"]
+            "firp_gemm_static_capacity", "firp_debug_gemm_static", "firp_get_event_overhead", "firp_get_stat"]
 
 
 def _i32(a) -> np.ndarray:
@@ -291,6 +292,12 @@ class Engine:
         self._check(self.lib.firp_get_drafts(self.ctx, _p(d), _p(valid)))
         return d[:, : self.k], valid.tolist()
 
+    def drafts_valid_host(self) -> List[int]:
+        """Whether each sequence has drafts for its next step (the host's mirror: no device work)."""
+        valid = np.zeros(self.batch, dtype=np.int32)
+        self._check(self.lib.firp_get_drafts(self.ctx, None, _p(valid)))
+        return valid.tolist()
+
     def ctx_len(self) -> List[int]:
         n = np.zeros(self.batch, dtype=np.int32)
         self._check(self.lib.firp_get_ctx_len(self.ctx, _p(n)))
@@ -301,6 +308,11 @@ class Engine:
         n, ms, by = C.c_int64(0), C.c_double(0), C.c_double(0)
         self._check(self.lib.firp_get_gemm_timing(self.ctx, C.byref(n), C.byref(ms), C.byref(by)))
         return n.value, ms.value, by.value
+
+    def stat(self, name: str) -> int:
+        v = C.c_int64(0)
+        self._check(self.lib.firp_get_stat(self.ctx, name.encode(), C.byref(v)))
+        return v.value
 
     def event_bracket_us(self) -> float:
         """Mean reading (microseconds) of an empty pair of events on the library's stream."""
@@ -318,14 +330,17 @@ class Engine:
 
 
 def engine_for_config(cfg, weights, *, max_ctx: int, max_batch: int = 1, max_nodes: int = 64, max_rows: int = 128,
-                      b_max: int = 8, gemm: Optional[int] = None) -> Engine:
-    """An Engine for a synthetic model configuration (synth.ModelConfig) and its weight dict."""
+                      b_max: int = 8, gemm: Optional[int] = None, keep_logits: bool = False) -> Engine:
+    """An Engine for a synthetic model configuration (synth.ModelConfig) and its weight dict.
+    `keep_logits`: every step also writes all its logits (read back with Engine.last_logits)."""
     e = Engine(n_layers=cfg.n_layers, d_model=cfg.d_model, n_q_heads=cfg.n_q_heads, n_kv_heads=cfg.n_kv_heads,
                head_dim=cfg.head_dim, d_ffn=cfg.d_ffn, vocab=cfg.vocab, rms_eps=cfg.rms_eps, rope_base=cfg.rope_base,
                dtype=cfg.dtype, weights=weights, firp_layer=cfg.firp_layer, k=cfg.k, max_ctx=max_ctx,
                max_batch=max_batch, max_nodes=max_nodes, max_rows=max_rows, b_max=b_max, firp_layers=cfg.firp_layers)
     if gemm is not None:
         e.set_option("gemm", gemm)
+    if keep_logits:
+        e.set_option("keep_logits", 1)
     return e
 
 

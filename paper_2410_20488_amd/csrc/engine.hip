@@ -45,6 +45,21 @@ struct HostTree {
   }
 };
 
+// The per-row and per-node tables of one topology (device), one contiguous block per slot so
+// that a new topology is uploaded with a single copy.  A few slots are kept: decoding alternates
+// between the full tree and its root-only sub-tree (a path that ends at a non-anchor leaves no
+// drafts), and neither switch may cost an upload.
+#define FIRP_TOPO_SLOTS 4
+struct TopoLayout {   // byte offsets inside a slot
+  size_t seq, local, pos, mask, parent, level, rank, cstart, clist, pbase, psrc, bytes;
+};
+struct TopoSlot {
+  char* base = nullptr;
+  HostTree key;
+  bool valid = false;
+  unsigned long long last_use = 0;
+};
+
 }  // namespace
 
 struct firp_ctx {
@@ -55,6 +70,9 @@ struct firp_ctx {
   int gemm_kind = 0;    // 0 plain, 1 MFMA
   int attn_kind = 0;    // 0 plain, 1 MFMA flash-decode (needs the bf16 planes of q)
   bool cache_clean = false;  // the KV cache holds only finite values (zero-filled once)
+  bool keep_logits = false;  // option "keep_logits": the lm-head's consumer also writes all logits
+  bool force_logits = false; // ... for the running call only (the training forward reads them)
+  bool last_has_logits = false;
   float* attn_scratch = nullptr;
   void* argmax_scratch = nullptr;
   bf16* q_frag = nullptr;      // q of the running layer as MFMA fragments (MFMA attention)
@@ -92,7 +110,12 @@ struct firp_ctx {
   int batch = 0;
   bool prefilled = false;
   std::vector<int> p0, drafts_valid;
-  HostTree cur;          // topology whose tables are on the device
+  TopoLayout tl_off{};
+  TopoSlot slot[FIRP_TOPO_SLOTS + 1];   // the last one: prefill chunks and the training forward (never cached)
+  int cur_slot = -1;     // slot the table pointers above point into
+  unsigned long long use_clock = 0;
+  long topo_uploads = 0;  // topologies uploaded since firp_init (a cached one costs none)
+  HostTree cur;          // topology of the current slot
   bool tables_valid = false;
   int last_rows = 0, last_N = 0, last_P = 0, last_steps = 0;  // last_steps: pseudo rows per anchor
   // optional timing of the projection launches (HIP events on the library's stream)
@@ -192,18 +215,31 @@ size_t carve(firp_ctx* c, char* base) {
   size_t kv_elems = (size_t)d.max_batch * c->kv_seq_stride;
   c->kcache = cv.take<char>(kv_elems * es);
   c->vcache = cv.take<char>(kv_elems * es);
-  c->rt_seq = cv.take<int>(R);
-  c->rt_local = cv.take<int>(R);
-  c->rt_pos = cv.take<int>(R);
-  c->rt_mask = cv.take<unsigned long long>((size_t)R * FIRP_MASK_WORDS);
-  int N = d.max_rows;  // prefill chunks use the node tables' row arrays only
-  c->tt_parent = cv.take<int>(N);
-  c->tt_level = cv.take<int>(N);
-  c->tt_rank = cv.take<int>(N);
-  c->tt_cstart = cv.take<int>(N + 1);
-  c->tt_clist = cv.take<int>(N);
-  c->tt_pbase = cv.take<int>(N);
-  c->pseudo_src = cv.take<int>(R);
+  {
+    // layout of one slot (R rows, N nodes)
+    Carver lay{nullptr};
+    auto off = [&](size_t bytes) {
+      lay.off = align_up(lay.off, 256);
+      size_t o = lay.off;
+      lay.off += bytes;
+      return o;
+    };
+    int N = d.max_rows;  // prefill chunks use the node tables' row arrays only
+    TopoLayout& t = c->tl_off;
+    t.seq = off((size_t)R * 4);
+    t.local = off((size_t)R * 4);
+    t.pos = off((size_t)R * 4);
+    t.mask = off((size_t)R * FIRP_MASK_WORDS * 8);
+    t.parent = off((size_t)N * 4);
+    t.level = off((size_t)N * 4);
+    t.rank = off((size_t)N * 4);
+    t.cstart = off((size_t)(N + 1) * 4);
+    t.clist = off((size_t)N * 4);
+    t.pbase = off((size_t)N * 4);
+    t.psrc = off((size_t)R * 4);
+    t.bytes = align_up(lay.off, 256);
+    for (auto& sl : c->slot) sl.base = cv.take<char>(t.bytes);
+  }
   c->injected = cv.take<int>(R);
   int B = d.max_batch;
   c->st.p0 = cv.take<int>(B);
@@ -257,6 +293,23 @@ RowTab row_tab(const firp_ctx* c) { return RowTab{c->rt_seq, c->rt_local, c->rt_
 TreeTab tree_tab(const firp_ctx* c, int N, int P) {
   return TreeTab{c->tt_parent, c->tt_level, c->tt_rank, c->tt_cstart, c->tt_clist, c->tt_pbase, N, P,
                  c->k > 0 ? P / c->k : 0};
+}
+
+void select_slot(firp_ctx* c, int i) {
+  char* b = c->slot[i].base;
+  const TopoLayout& t = c->tl_off;
+  c->rt_seq = (int*)(b + t.seq);
+  c->rt_local = (int*)(b + t.local);
+  c->rt_pos = (int*)(b + t.pos);
+  c->rt_mask = (unsigned long long*)(b + t.mask);
+  c->tt_parent = (int*)(b + t.parent);
+  c->tt_level = (int*)(b + t.level);
+  c->tt_rank = (int*)(b + t.rank);
+  c->tt_cstart = (int*)(b + t.cstart);
+  c->tt_clist = (int*)(b + t.clist);
+  c->tt_pbase = (int*)(b + t.pbase);
+  c->pseudo_src = (int*)(b + t.psrc);
+  c->cur_slot = i;
 }
 
 // y = act . W^T into the partial-sum buffer at column `col` of rows that are `ld` wide.
@@ -404,7 +457,12 @@ firp_status forward(firp_ctx* c, int B, int N, int n_anchor, bool head, int max_
       launch_add_rmsnorm(c->x, pending, rows, d.d_model, c->norm_final, c->dtype, c->act_d, sp, c->norm_ss, s);
       Partial lg = project(c, c->act_d, c->lm_head, c->packed ? c->pk_head : nullptr, rows, d.vocab, d.d_model,
                            d.vocab, 0, nullptr);
-      launch_argmax_topb(lg, rs, c->logits, real_rows, rows, d.vocab, d.b_max, c->st.amax, c->st.top, c->argmax_scratch, s);
+      // the logits themselves are written only on request (tests, the training forward): the step
+      // needs the greedy token of every node and the top-b ids of every pseudo row, nothing else
+      const bool want_logits = c->keep_logits || c->force_logits;
+      launch_argmax_topb(lg, rs, want_logits ? c->logits : nullptr, real_rows, rows, d.vocab, d.b_max, c->st.amax,
+                         c->st.top, c->argmax_scratch, s);
+      c->last_has_logits = want_logits;
       break;
     }
     // the pending partials cover `pending_rows` rows; rows beyond (new pseudo rows) have none
@@ -446,7 +504,26 @@ firp_status forward(firp_ctx* c, int B, int N, int n_anchor, bool head, int max_
 firp_status upload_tree(firp_ctx* c, int B, const std::vector<int>& parent, const std::vector<int>& rank,
                         const std::vector<uint8_t>& anchor) {
   int N = (int)parent.size(), k = c->k;
-  if (c->tables_valid && c->cur.same(B, k, parent, rank, anchor)) return FIRP_OK;
+  ++c->use_clock;
+  // a topology seen before still has its tables on the device
+  for (int i = 0; i < FIRP_TOPO_SLOTS; ++i) {
+    TopoSlot& sl = c->slot[i];
+    if (sl.valid && sl.key.same(B, k, parent, rank, anchor)) {
+      sl.last_use = c->use_clock;
+      if (c->cur_slot != i) select_slot(c, i);
+      c->cur = sl.key;
+      c->tables_valid = true;
+      return FIRP_OK;
+    }
+  }
+  int victim = 0;
+  for (int i = 0; i < FIRP_TOPO_SLOTS; ++i) {
+    if (!c->slot[i].valid) {
+      victim = i;
+      break;
+    }
+    if (c->slot[i].last_use < c->slot[victim].last_use) victim = i;
+  }
   std::vector<int> depth(N, 0), pbase(N, -1), cstart(N + 1, 0), clist(std::max(N - 1, 1), 0);
   std::vector<std::vector<unsigned long long>> m(N, std::vector<unsigned long long>(FIRP_MASK_WORDS, 0));
   int n_anchor = 0;
@@ -465,15 +542,21 @@ firp_status upload_tree(firp_ctx* c, int B, const std::vector<int>& parent, cons
     for (int v = 1; v < N; ++v) clist[fill[parent[v]]++] = v;  // ascending node id per parent
   }
   int P = k * n_anchor, T = N + P, R = B * T;
-  std::vector<int> seq(R), local(R), pos(R), psrc(std::max(B * n_anchor, 1));
-  std::vector<unsigned long long> mask((size_t)R * FIRP_MASK_WORDS);
+  // one host image of the slot, one copy
+  const TopoLayout& t = c->tl_off;
+  std::vector<char> img(t.bytes, 0);
+  int* seq = (int*)(img.data() + t.seq);
+  int* local = (int*)(img.data() + t.local);
+  int* pos = (int*)(img.data() + t.pos);
+  unsigned long long* mask = (unsigned long long*)(img.data() + t.mask);
+  int* psrc = (int*)(img.data() + t.psrc);
   for (int b = 0; b < B; ++b) {
     for (int v = 0; v < N; ++v) {
       int r = b * N + v;
       seq[r] = b;
       local[r] = v;
       pos[r] = depth[v];
-      std::copy(m[v].begin(), m[v].end(), mask.begin() + (size_t)r * FIRP_MASK_WORDS);
+      std::copy(m[v].begin(), m[v].end(), mask + (size_t)r * FIRP_MASK_WORDS);
     }
     for (int v = 0; v < N; ++v) {
       if (pbase[v] < 0) continue;
@@ -488,33 +571,37 @@ firp_status upload_tree(firp_ctx* c, int B, const std::vector<int>& parent, cons
         seq[r] = b;
         local[r] = loc;
         pos[r] = depth[v] + i + 1;
-        std::copy(mm.begin(), mm.end(), mask.begin() + (size_t)r * FIRP_MASK_WORDS);
+        std::copy(mm.begin(), mm.end(), mask + (size_t)r * FIRP_MASK_WORDS);
       }
     }
   }
+  (void)R;
+  std::copy(parent.begin(), parent.end(), (int*)(img.data() + t.parent));
+  std::copy(depth.begin(), depth.end(), (int*)(img.data() + t.level));
+  std::copy(rank.begin(), rank.end(), (int*)(img.data() + t.rank));
+  std::copy(cstart.begin(), cstart.end(), (int*)(img.data() + t.cstart));
+  std::copy(clist.begin(), clist.end(), (int*)(img.data() + t.clist));
+  std::copy(pbase.begin(), pbase.end(), (int*)(img.data() + t.pbase));
   hipStream_t s = c->stream;
-  HIPCHK(hipStreamSynchronize(s));  // the previous step may still read the old tables
-  HIPCHK(hipMemcpy(c->rt_seq, seq.data(), R * sizeof(int), hipMemcpyHostToDevice));
-  HIPCHK(hipMemcpy(c->rt_local, local.data(), R * sizeof(int), hipMemcpyHostToDevice));
-  HIPCHK(hipMemcpy(c->rt_pos, pos.data(), R * sizeof(int), hipMemcpyHostToDevice));
-  HIPCHK(hipMemcpy(c->rt_mask, mask.data(), mask.size() * sizeof(unsigned long long), hipMemcpyHostToDevice));
-  HIPCHK(hipMemcpy(c->tt_parent, parent.data(), N * sizeof(int), hipMemcpyHostToDevice));
-  HIPCHK(hipMemcpy(c->tt_level, depth.data(), N * sizeof(int), hipMemcpyHostToDevice));
-  HIPCHK(hipMemcpy(c->tt_rank, rank.data(), N * sizeof(int), hipMemcpyHostToDevice));
-  HIPCHK(hipMemcpy(c->tt_cstart, cstart.data(), (N + 1) * sizeof(int), hipMemcpyHostToDevice));
-  HIPCHK(hipMemcpy(c->tt_clist, clist.data(), clist.size() * sizeof(int), hipMemcpyHostToDevice));
-  HIPCHK(hipMemcpy(c->tt_pbase, pbase.data(), N * sizeof(int), hipMemcpyHostToDevice));
-  HIPCHK(hipMemcpy(c->pseudo_src, psrc.data(), psrc.size() * sizeof(int), hipMemcpyHostToDevice));
-  c->cur.B = B;
-  c->cur.N = N;
-  c->cur.P = P;
-  c->cur.k = k;
-  c->cur.n_anchor = n_anchor;
-  c->cur.parent = parent;
-  c->cur.rank = rank;
-  c->cur.anchor = anchor;
-  c->cur.depth = depth;
-  c->cur.max_depth = *std::max_element(depth.begin(), depth.end());
+  TopoSlot& sl = c->slot[victim];
+  sl.valid = false;
+  HIPCHK(hipStreamSynchronize(s));  // an earlier step may still read the slot that is overwritten
+  HIPCHK(hipMemcpy(sl.base, img.data(), t.bytes, hipMemcpyHostToDevice));
+  ++c->topo_uploads;
+  sl.key.B = B;
+  sl.key.N = N;
+  sl.key.P = P;
+  sl.key.k = k;
+  sl.key.n_anchor = n_anchor;
+  sl.key.parent = parent;
+  sl.key.rank = rank;
+  sl.key.anchor = anchor;
+  sl.key.depth = depth;
+  sl.key.max_depth = *std::max_element(depth.begin(), depth.end());
+  sl.valid = true;
+  sl.last_use = c->use_clock;
+  select_slot(c, victim);
+  c->cur = sl.key;
   c->tables_valid = true;
   return FIRP_OK;
 }
@@ -797,6 +884,7 @@ firp_status firp_prefill(firp_ctx* c, int32_t batch, const int32_t* tokens, cons
     local[j] = pos[j] = j;
     for (int i = 0; i <= j; ++i) mask[(size_t)j * FIRP_MASK_WORDS + (i >> 6)] |= 1ull << (i & 63);
   }
+  select_slot(c, FIRP_TOPO_SLOTS);   // the chunk tables live in the slot that is never cached
   HIPCHK(hipStreamSynchronize(s));
   HIPCHK(hipMemcpy(c->rt_local, local.data(), C * sizeof(int), hipMemcpyHostToDevice));
   HIPCHK(hipMemcpy(c->rt_pos, pos.data(), C * sizeof(int), hipMemcpyHostToDevice));
@@ -869,6 +957,7 @@ firp_status firp_train_forward(firp_ctx* c, const int32_t* tokens, int32_t n, in
     psrc[v] = v;
   }
   c->tables_valid = false;
+  select_slot(c, FIRP_TOPO_SLOTS);
   HIPCHK(hipStreamSynchronize(s));
   HIPCHK(hipMemcpy(c->rt_seq, seq.data(), R * sizeof(int), hipMemcpyHostToDevice));
   HIPCHK(hipMemcpy(c->rt_local, local.data(), R * sizeof(int), hipMemcpyHostToDevice));
@@ -877,7 +966,9 @@ firp_status firp_train_forward(firp_ctx* c, const int32_t* tokens, int32_t n, in
   HIPCHK(hipMemcpy(c->pseudo_src, psrc.data(), n * sizeof(int), hipMemcpyHostToDevice));
   HIPCHK(hipMemcpy(c->st.tok, tokens, n * sizeof(int), hipMemcpyHostToDevice));
   launch_set_root(c->st, 0, tokens[0], 0, s);   // cache length 0
+  c->force_logits = true;   // the KL terms are formed from the logits
   st = forward(c, 1, n, n, true, 0, 0, step - 1, step);
+  c->force_logits = false;
   if (st != FIRP_OK) return st;
   float* d_kl = (float*)c->attn_scratch;   // free again once the last attention has run
   launch_kl_rows(c->logits, c->d.vocab, n, step, d_kl, s);
@@ -931,6 +1022,7 @@ firp_status firp_debug_last_logits(firp_ctx* c, float* logits, int32_t* n_rows) 
   if (!c) return FIRP_EINVAL;
   if (!logits || !n_rows) return c->fail(FIRP_EINVAL, "argument pointer is NULL");
   if (c->last_rows == 0) return c->fail(FIRP_ESTATE, "no step has run");
+  if (!c->last_has_logits) return c->fail(FIRP_ESTATE, "the last step did not keep its logits (option \"keep_logits\")");
   int B = c->batch, N = c->last_N, P = c->last_P, T = N + P, V = c->d.vocab;
   HIPCHK(hipStreamSynchronize(c->stream));
   for (int b = 0; b < B; ++b) {
@@ -960,11 +1052,13 @@ firp_status firp_debug_last_path(firp_ctx* c, int32_t* path_nodes) {
 firp_status firp_get_drafts(const firp_ctx* cc, int32_t* drafts, int32_t* valid) {
   firp_ctx* c = const_cast<firp_ctx*>(cc);
   if (!c) return FIRP_EINVAL;
-  if (!drafts || !valid) return c->fail(FIRP_EINVAL, "argument pointer is NULL");
+  if (!valid) return c->fail(FIRP_EINVAL, "argument pointer is NULL");
   if (!c->prefilled) return c->fail(FIRP_ESTATE, "no sequence is running");
-  HIPCHK(hipStreamSynchronize(c->stream));
-  if (c->k > 0)
-    HIPCHK(hipMemcpy(drafts, c->st.drafts, (size_t)c->batch * c->k * c->d.b_max * sizeof(int), hipMemcpyDeviceToHost));
+  if (drafts) {   // (without it only the flags are wanted: they are mirrored on the host)
+    HIPCHK(hipStreamSynchronize(c->stream));
+    if (c->k > 0)
+      HIPCHK(hipMemcpy(drafts, c->st.drafts, (size_t)c->batch * c->k * c->d.b_max * sizeof(int), hipMemcpyDeviceToHost));
+  }
   for (int b = 0; b < c->batch; ++b) valid[b] = c->drafts_valid[b];
   return FIRP_OK;
 }
@@ -1033,6 +1127,11 @@ firp_status firp_set_option(firp_ctx* c, const char* name, int32_t value) {
     }
     return c->fail(FIRP_EINVAL, "attention kind %d is not available for this model", value);
   }
+  if (!strcmp(name, "keep_logits")) {
+    if (value != 0 && value != 1) return c->fail(FIRP_EINVAL, "keep_logits takes 0 or 1");
+    c->keep_logits = value != 0;
+    return FIRP_OK;
+  }
   if (!strcmp(name, "time_gemm")) {
     if (value != 0 && value != 1) return c->fail(FIRP_EINVAL, "time_gemm takes 0 or 1");
     if (value && c->ev.empty()) {
@@ -1063,6 +1162,17 @@ firp_status firp_get_gemm_timing(const firp_ctx* c, int64_t* launches, double* t
   if (total_ms) *total_ms = c->gemm_ms;
   if (weight_bytes) *weight_bytes = c->gemm_bytes;
   return FIRP_OK;
+}
+
+firp_status firp_get_stat(const firp_ctx* cc, const char* name, int64_t* value) {
+  firp_ctx* c = const_cast<firp_ctx*>(cc);
+  if (!c) return FIRP_EINVAL;
+  if (!name || !value) return c->fail(FIRP_EINVAL, "argument pointer is NULL");
+  if (!strcmp(name, "topo_uploads")) {
+    *value = c->topo_uploads;
+    return FIRP_OK;
+  }
+  return c->fail(FIRP_EINVAL, "unknown statistic '%s'", name);
 }
 
 firp_status firp_get_event_overhead(const firp_ctx* c, double* bracket_ms) {

@@ -12,6 +12,7 @@ from tests.helpers import cpu_weights, make_oracle
 
 
 def make_engine(cfg: synth.ModelConfig, weights, **kw) -> binding.Engine:
+    kw.setdefault("keep_logits", True)     # the tests compare all logits of every step
     return binding.engine_for_config(cfg, weights, **kw)
 
 

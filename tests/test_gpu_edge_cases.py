@@ -122,3 +122,47 @@ def test_one_token_prompt_and_full_context(progress):
     assert full + 4 > 12                       # no room for a root plus three levels
     eng.reset()
     assert eng.prefill([prompt]) == [orc.fork().prefill(prompt)]
+
+
+@pytest.mark.parametrize("name,tol", [("tiny", 1e-4), ("tiny_bf16", 2e-2)])
+def test_full_tree_and_root_only_tree_alternate_without_uploads(progress, name, tol):
+    """With the root as the only anchor, a step that accepts a candidate ends on a node without
+    pseudo rows, so the next step has no drafts and runs on the root alone; the one after runs
+    the full tree again.  Twenty steps of that alternation in lockstep with the oracle; the
+    library keeps both topologies on the device, so the whole run uploads exactly two."""
+    cfg = synth.CONFIGS[name]
+    w = synth.make_weights(cfg, DEV, with_bias=True)
+    tree = synth.full_tree((3, 2), "root")
+    rep, eng, orc = run_lockstep(cfg, w, tree, prompt_len=40, n_steps=20, tol=tol, progress=progress, max_rows=32)
+    assert rep.steps == 20 and sum(rep.accepted_hist[2:]) >= 4      # planted continuations were accepted
+    assert eng.stat("topo_uploads") == 2, eng.stat("topo_uploads")
+    if name == "tiny":
+        assert rep.tie_ambiguous == 0
+    compare_cache(eng, orc, cfg)
+
+
+def test_more_topologies_than_the_library_keeps(progress):
+    """Six different trees in rotation on one engine (the library keeps four): every step is
+    checked against the oracle, whatever slot its tables were uploaded to or evicted from."""
+    cfg = synth.CONFIGS["tiny"]
+    w = synth.make_weights(cfg, DEV, with_bias=True)
+    orc = make_oracle(cfg, cpu_weights(w), dtype=torch.float64)
+    eng = make_engine(cfg, w, max_ctx=200, max_nodes=16, max_rows=64)
+    trees = [synth.full_tree((3, 2), "root"), synth.full_tree((2, 2, 2), "all"), synth.chain_tree(3, "root"),
+             synth.random_tree(4, 12, 3, 4, 0.5), synth.full_tree((4,), "all"), synth.random_tree(9, 9, 2, 3, 1.0)]
+    trees = [synth.Tree(t.parent, t.rank, (1,) + tuple(t.anchor[1:])) for t in trees]   # root an anchor: drafts stay valid
+    prompt = synth.prompt_tokens(cfg.seed, 25, cfg.vocab).tolist()
+    assert eng.prefill([prompt]) == [orc.prefill(prompt)]
+    for step in range(18):
+        t = trees[step % len(trees)]
+        args = dict(parent=list(t.parent), rank=list(t.rank), anchor=list(t.anchor))
+        r = orc.step(**args)
+        got = eng.step(args["parent"], args["rank"], args["anchor"])[0]
+        assert got == r.tokens and eng.last_path()[0] == r.path, f"step {step}"
+        lg = eng.last_logits()[0]
+        ref = r.logits.numpy()
+        assert lg.shape == ref.shape and np.abs(lg - ref).max() / ref.std() < 1e-4, f"step {step}"
+        if r.drafts is not None:
+            assert eng.drafts()[0][0].tolist() == r.drafts
+    # 1 (the prefill's root-only step) + 6 first uses + the re-uploads of evicted ones
+    assert eng.stat("topo_uploads") >= 7
