@@ -163,6 +163,8 @@ def main() -> int:
                          "continuation so that 0, 1, .. k candidates are accepted in rotation, as trained maps would "
                          "have it: with the root as the only anchor every step that accepts a candidate is followed "
                          "by a root-only step (no drafts)")
+    ap.add_argument("--no-graph", action="store_true", help="launch every kernel of a step directly instead of "
+                                                            "replaying the step as a captured HIP graph")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a plain 1 GiB device copy three times (reference for scaling the "
@@ -204,6 +206,8 @@ def main() -> int:
     total_steps = args.warmup + args.steps + 16 + (2 * (args.warmup + args.steps) if args.accept_pattern else 0)
     eng = binding.engine_for_config(cfg, weights, max_ctx=prompt_len + (cfg.k + 1) * (total_steps + 2) + 8,
                       max_batch=args.batch, max_nodes=tree.n_nodes, max_rows=max(128, t_hi), b_max=8)
+    if args.no_graph:
+        eng.set_option("graph", 0)
     prompts = [synth.prompt_tokens(cfg.seed, prompt_len, cfg.vocab, stream=b).tolist() for b in range(args.batch)]
     prompt = prompts[0]
     eng.prefill(prompts)
@@ -232,6 +236,7 @@ def main() -> int:
         ms_per_step = (t1 - t0) * 1e3 / args.steps
     pct = lambda q: per_step[min(len(per_step) - 1, int(q * len(per_step)))]
 
+    graph_launches = eng.stat("graph_launches")
     # roofline of the dominant kernel (the weight-streaming projection): HIP events on the
     # library's stream around every launch, over 16 further steps
     eng.set_option("time_gemm", 1)
@@ -268,6 +273,7 @@ def main() -> int:
         "step_frac_of_stream_read_ceiling": round(step_gbs / ceiling_gbs, 4),
         "tokens_per_step": round(tokens / args.steps / args.batch, 3),
         "setup_s": round(setup_s, 1),
+        "steps_replayed_as_hip_graph": graph_launches,
         "roofline": {"bound": "hbm", "kernel": "k_gemm_mfma", "achieved": round(gemm_gbs, 1), "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": round(gemm_gbs / HBM_PEAK_GBS, 4),
                      "traffic": (round(prof["traffic_ratio"] * gemm_bytes / max(launches, 1), 0)

@@ -195,7 +195,11 @@ class Engine:
             # test aid: a workspace of NaN bit patterns shows any read of memory the library has not written
             self.workspace.fill_(0xFF)
         base = (self.workspace.data_ptr() + 255) // 256 * 256
-        self.stream = stream if stream is not None else torch.cuda.current_stream(dev)
+        # a stream of its own (default priority): the library replays the step as a captured graph,
+        # which the legacy default stream does not allow; everything queued so far (the weights) must
+        # be complete before that stream reads it
+        self.stream = stream if stream is not None else torch.cuda.Stream(device=dev)
+        torch.cuda.synchronize(dev)
         ctx = C.c_void_p()
         pwp = None if pw is None else C.cast(pw, C.POINTER(C.c_void_p))
         pbp = None if pb is None else C.cast(pb, C.POINTER(C.c_void_p))

@@ -192,7 +192,7 @@ template <int DH>
 __global__ __launch_bounds__(64 * NWAVES, 1) void k_attention_mfma(const bf16* __restrict__ q_frag,
                                                           int n_q_heads, SeqRows sr, int n_local,
                                                           const unsigned long long* __restrict__ row_mask,
-                                                          const int* __restrict__ p0v, int seq0, KvView kv, int chunk,
+                                                          const int* __restrict__ p0v, int seq0, KvView kv,
                                                           float* __restrict__ part_o, float* __restrict__ part_ml,
                                                           int splits) {
   constexpr int DS = DH / 32;       // k-steps of the score product
@@ -206,13 +206,26 @@ __global__ __launch_bounds__(64 * NWAVES, 1) void k_attention_mfma(const bf16* _
   const int G = n_q_heads / kv.n_kv_heads;
   const int n_tiles = (n_local + 15) >> 4;
   const int n_pairs = n_tiles * G;
-  const int key_begin = split * chunk;
-  // last block the launch geometry allows: the first fetches go out against this bound, before
-  // the committed length has even arrived
-  const int hard_last = (min(key_begin + chunk, kv.slots) - key_begin - 32) >> 5;
   const int bs = seq0 + b;   // sequence whose cache this launch reads (b counts inside the launch)
   const int p0 = p0v[bs];
   const int n_keys = p0 + n_local;
+  // The sequence's keys in `splits` chunks of whole 32-key blocks.  The chunk length follows
+  // from the committed length on the device, so that no launch argument changes from step to
+  // step (a captured launch can be replayed as the context grows).
+  const int chunk = ((((n_keys + 31) >> 5) + splits - 1) / splits) << 5;
+  const int key_begin = split * chunk;
+  if (key_begin >= n_keys) {
+    // a split past the end of a short context: leave the neutral element (weight 0) for the merge
+    for (int idx = threadIdx.x; idx < n_local * G; idx += blockDim.x) {
+      const int local = idx / G, head = hk * G + idx % G;
+      const size_t base = ((size_t)global_row(sr, b, local) * n_q_heads + head) * splits + split;
+      part_ml[base * 2 + 0] = -__builtin_inff();
+      part_ml[base * 2 + 1] = 0.f;
+    }
+    return;
+  }
+  // last block the launch geometry allows (key_begin < n_keys <= slots, both multiples of 32 apart)
+  const int hard_last = (min(key_begin + chunk, kv.slots) - key_begin - 32) >> 5;
   const int key_end = min(n_keys, key_begin + chunk);
   const int nb = key_end > key_begin ? (key_end - key_begin + 31) >> 5 : 0;   // blocks of this chunk
   const int last = nb - 1;
@@ -516,22 +529,21 @@ void launch_attention_mfma(const bf16* q_frag, int rows, int n_q_heads, int B, i
   const int n_local = n_real_per_seq + n_pseudo_per_seq;
   const int dh = kv.head_dim;
   SeqRows sr{n_real_per_seq, std::max(1, n_anchor_per_seq), B * n_real_per_seq, B * n_anchor_per_seq};
-  // chunks of whole 32-key blocks; about one workgroup per CU
+  // about one workgroup per CU; the count of splits depends on the context length only while the
+  // context is shorter than that many 32-key blocks
   int n_keys = max_ctx_now + n_local;
   int blocks = (n_keys + 31) / 32;
   int want = std::max(1, 256 / std::max(1, kv.n_kv_heads * B));
   int splits = std::max(1, std::min({want, blocks, FIRP_ATTN_MAX_SPLITS}));
-  int chunk = ((blocks + splits - 1) / splits) * 32;
-  splits = (n_keys + chunk - 1) / chunk;
   float* part_o = scratch;
   float* part_ml = scratch + (size_t)rows * n_q_heads * FIRP_ATTN_MAX_SPLITS * dh;
   dim3 g(splits, kv.n_kv_heads, B), blk(64 * NWAVES);
   if (dh == 128)
-    hipLaunchKernelGGL(k_attention_mfma<128>, g, blk, 0, s, q_frag, n_q_heads, sr, n_local, rt.mask, p0, seq0, kv, chunk, part_o, part_ml, splits);
+    hipLaunchKernelGGL(k_attention_mfma<128>, g, blk, 0, s, q_frag, n_q_heads, sr, n_local, rt.mask, p0, seq0, kv, part_o, part_ml, splits);
   else if (dh == 64)
-    hipLaunchKernelGGL(k_attention_mfma<64>, g, blk, 0, s, q_frag, n_q_heads, sr, n_local, rt.mask, p0, seq0, kv, chunk, part_o, part_ml, splits);
+    hipLaunchKernelGGL(k_attention_mfma<64>, g, blk, 0, s, q_frag, n_q_heads, sr, n_local, rt.mask, p0, seq0, kv, part_o, part_ml, splits);
   else
-    hipLaunchKernelGGL(k_attention_mfma<32>, g, blk, 0, s, q_frag, n_q_heads, sr, n_local, rt.mask, p0, seq0, kv, chunk, part_o, part_ml, splits);
+    hipLaunchKernelGGL(k_attention_mfma<32>, g, blk, 0, s, q_frag, n_q_heads, sr, n_local, rt.mask, p0, seq0, kv, part_o, part_ml, splits);
   int hpb = std::max(1, 256 / (dh / 4));
   dim3 gc(rows, (n_q_heads + hpb - 1) / hpb), bc(dh / 4, hpb);
   hipLaunchKernelGGL(k_attn_combine<true>, gc, bc, 0, s, part_o, part_ml, splits, n_q_heads, dh, out);

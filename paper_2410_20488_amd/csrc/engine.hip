@@ -53,11 +53,24 @@ struct HostTree {
 struct TopoLayout {   // byte offsets inside a slot
   size_t seq, local, pos, mask, parent, level, rank, cstart, clist, pbase, psrc, bytes;
 };
+// What a captured step depends on besides the topology: when any of it differs, the step is
+// captured again.
+struct GraphKey {
+  int B = 0, injected = 0, keep_logits = 0, gemm_kind = 0, attn_kind = 0;
+  bool operator==(const GraphKey& o) const {
+    return B == o.B && injected == o.injected && keep_logits == o.keep_logits && gemm_kind == o.gemm_kind &&
+           attn_kind == o.attn_kind;
+  }
+};
 struct TopoSlot {
   char* base = nullptr;
   HostTree key;
   bool valid = false;
   unsigned long long last_use = 0;
+  // the decoding step on this topology as a captured graph: [0] with the library's own drafts,
+  // [1] with injected candidates
+  hipGraphExec_t exec[2] = {nullptr, nullptr};
+  GraphKey gkey[2];
 };
 
 }  // namespace
@@ -115,6 +128,9 @@ struct firp_ctx {
   int cur_slot = -1;     // slot the table pointers above point into
   unsigned long long use_clock = 0;
   long topo_uploads = 0;  // topologies uploaded since firp_init (a cached one costs none)
+  bool use_graph = true;     // option "graph": replay the step of a resident topology as a HIP graph
+  bool graph_broken = false; // the stream cannot be captured (e.g. the default stream): launch directly
+  long graph_launches = 0, graph_captures = 0;
   HostTree cur;          // topology of the current slot
   bool tables_valid = false;
   int last_rows = 0, last_N = 0, last_P = 0, last_steps = 0;  // last_steps: pseudo rows per anchor
@@ -585,6 +601,11 @@ firp_status upload_tree(firp_ctx* c, int B, const std::vector<int>& parent, cons
   hipStream_t s = c->stream;
   TopoSlot& sl = c->slot[victim];
   sl.valid = false;
+  for (auto& ex : sl.exec)
+    if (ex) {
+      (void)hipGraphExecDestroy(ex);
+      ex = nullptr;
+    }
   HIPCHK(hipStreamSynchronize(s));  // an earlier step may still read the slot that is overwritten
   HIPCHK(hipMemcpy(sl.base, img.data(), t.bytes, hipMemcpyHostToDevice));
   ++c->topo_uploads;
@@ -690,16 +711,75 @@ firp_status run_step(firp_ctx* c, const firp_tree* tree, const int32_t* node_tok
     HIPCHK(hipMemcpyAsync(c->injected, node_tokens, (size_t)B * N * sizeof(int), hipMemcpyHostToDevice, s));
     inj = c->injected;
   }
-  launch_fill_tokens(c->st, tree_tab(c, N, P), B, inj, s);
   const bool empty_bracket = c->time_gemm && c->ev_empty[0];
-  if (empty_bracket) {
-    (void)hipEventRecord(c->ev_empty[0], s);
-    (void)hipEventRecord(c->ev_empty[1], s);
+  // the step's kernels, from candidate fill to the KV commit
+  auto enqueue = [&]() -> firp_status {
+    launch_fill_tokens(c->st, tree_tab(c, N, P), B, inj, s);
+    if (empty_bracket) {
+      (void)hipEventRecord(c->ev_empty[0], s);
+      (void)hipEventRecord(c->ev_empty[1], s);
+    }
+    firp_status fs = forward(c, B, N, n_anchor, true, ctx_max, 0, 0, c->k);
+    if (fs != FIRP_OK) return fs;
+    launch_verify_select(c->st, tree_tab(c, N, P), B, s);
+    launch_kv_compact(kv_view(c, 0), c->kv_layer_stride, c->d.n_layers, B, c->st, c->dtype, s);
+    return FIRP_OK;
+  };
+  // Replayed as a captured graph when nothing the kernels are launched with can change between
+  // steps: MFMA kernels (the attention launch takes its chunk length from the device), a
+  // context long enough that the number of attention splits no longer depends on it, packed
+  // weights in place, no event brackets.  Everything else the kernels read is device state.
+  const int want_splits = std::min(FIRP_ATTN_MAX_SPLITS, std::max(1, 256 / std::max(1, c->d.n_kv_heads * B)));
+  int ctx_min = ctx_max;
+  for (int b = 0; b < B; ++b) ctx_min = std::min(ctx_min, c->p0[b]);
+  const bool graphable = c->use_graph && !c->graph_broken && !c->time_gemm && c->attn_kind == 1 && c->split &&
+                         c->gemm_kind == 1 && c->packed && c->cur_slot >= 0 && c->cur_slot < FIRP_TOPO_SLOTS &&
+                         (ctx_min + N) / 32 >= want_splits;
+  bool launched = false;
+  if (graphable) {
+    TopoSlot& sl = c->slot[c->cur_slot];
+    GraphKey key;
+    key.B = B;
+    key.injected = inj ? 1 : 0;
+    key.keep_logits = c->keep_logits ? 1 : 0;
+    key.gemm_kind = c->gemm_kind;
+    key.attn_kind = c->attn_kind;
+    hipGraphExec_t& exec = sl.exec[key.injected];
+    if (exec && !(sl.gkey[key.injected] == key)) {
+      (void)hipGraphExecDestroy(exec);
+      exec = nullptr;
+    }
+    if (!exec) {
+      if (hipStreamBeginCapture(s, hipStreamCaptureModeThreadLocal) != hipSuccess) {
+        (void)hipGetLastError();
+        c->graph_broken = true;
+      } else {
+        firp_status fs = enqueue();
+        hipGraph_t g = nullptr;
+        hipError_t e = hipStreamEndCapture(s, &g);
+        if (fs == FIRP_OK && e == hipSuccess && g && hipGraphInstantiate(&exec, g, nullptr, nullptr, 0) == hipSuccess) {
+          sl.gkey[key.injected] = key;
+          ++c->graph_captures;
+        } else {
+          (void)hipGetLastError();
+          exec = nullptr;
+          c->graph_broken = true;
+        }
+        if (g) (void)hipGraphDestroy(g);
+        if (fs != FIRP_OK) return fs;
+      }
+    }
+    if (exec) {
+      HIPCHK(hipGraphLaunch(exec, s));
+      c->last_has_logits = c->keep_logits;
+      ++c->graph_launches;
+      launched = true;
+    }
   }
-  st = forward(c, B, N, n_anchor, true, ctx_max, 0, 0, c->k);
-  if (st != FIRP_OK) return st;
-  launch_verify_select(c->st, tree_tab(c, N, P), B, s);
-  launch_kv_compact(kv_view(c, 0), c->kv_layer_stride, c->d.n_layers, B, c->st, c->dtype, s);
+  if (!launched) {
+    st = enqueue();
+    if (st != FIRP_OK) return st;
+  }
   HIPCHK(hipMemcpyAsync(c->h_result, c->st.result, (size_t)B * FIRP_RESULT_STRIDE * sizeof(int), hipMemcpyDeviceToHost, s));
   HIPCHK(hipStreamSynchronize(s));
   for (size_t i = 0; i + 1 < c->ev_used; i += 2) {
@@ -843,6 +923,9 @@ void firp_destroy(firp_ctx* c) {
   for (auto& e : c->ev) (void)hipEventDestroy(e);
   for (auto& e : c->ev_empty)
     if (e) (void)hipEventDestroy(e);
+  for (auto& sl : c->slot)
+    for (auto& ex : sl.exec)
+      if (ex) (void)hipGraphExecDestroy(ex);
   if (c->h_result) {
     if (c->h_result_pinned)
       (void)hipHostFree(c->h_result);
@@ -1127,6 +1210,11 @@ firp_status firp_set_option(firp_ctx* c, const char* name, int32_t value) {
     }
     return c->fail(FIRP_EINVAL, "attention kind %d is not available for this model", value);
   }
+  if (!strcmp(name, "graph")) {
+    if (value != 0 && value != 1) return c->fail(FIRP_EINVAL, "graph takes 0 or 1");
+    c->use_graph = value != 0;
+    return FIRP_OK;
+  }
   if (!strcmp(name, "keep_logits")) {
     if (value != 0 && value != 1) return c->fail(FIRP_EINVAL, "keep_logits takes 0 or 1");
     c->keep_logits = value != 0;
@@ -1170,6 +1258,14 @@ firp_status firp_get_stat(const firp_ctx* cc, const char* name, int64_t* value) 
   if (!name || !value) return c->fail(FIRP_EINVAL, "argument pointer is NULL");
   if (!strcmp(name, "topo_uploads")) {
     *value = c->topo_uploads;
+    return FIRP_OK;
+  }
+  if (!strcmp(name, "graph_launches")) {
+    *value = c->graph_launches;
+    return FIRP_OK;
+  }
+  if (!strcmp(name, "graph_captures")) {
+    *value = c->graph_captures;
     return FIRP_OK;
   }
   return c->fail(FIRP_EINVAL, "unknown statistic '%s'", name);

@@ -120,3 +120,70 @@ def test_small_model_steps_are_bit_repeatable(dev, progress, name, seed):
             bad += 1
     progress(f"repeatability {name}: {bad} of 39 runs differ from the first")
     assert bad == 0
+
+
+@pytest.mark.parametrize("name", ["tiny_bf16", "tiny_gqa"])
+def test_captured_step_replays_match_direct_launches(name, dev, progress):
+    """The step of a resident topology is replayed as a captured HIP graph.  Two engines on the
+    same weights, one with the option off: every step (24 of them, alternating between a tree and
+    its root-only sub-tree as planted candidates are accepted, the context growing, eager work -
+    drafts read-outs, logits copies, synchronisations - between the replays) must give the same
+    tokens, paths, drafts and logits bit for bit; a third run repeats the first after a new
+    prefill on the same engine."""
+    import numpy as np
+    from tests.gpu_common import make_engine
+    cfg = synth.CONFIGS[name]
+    w = synth.make_weights(cfg, dev, with_bias=True)
+    tree = synth.full_tree((3, 2, 2)[:cfg.k], "root")
+    N = tree.n_nodes
+    args = (list(tree.parent), list(tree.rank), list(tree.anchor))
+    prompt = synth.prompt_tokens(cfg.seed + 5, 600, cfg.vocab).tolist()     # long enough for a fixed split count
+    eng_g = make_engine(cfg, w, max_ctx=800, max_nodes=N, max_rows=64)
+    eng_e = make_engine(cfg, w, max_ctx=800, max_nodes=N, max_rows=64)
+    eng_e.set_option("graph", 0)
+    ref = make_engine(cfg, w, max_ctx=800, max_nodes=1, max_rows=8)
+    ref.set_option("graph", 0)
+    kids = [[c for c in range(N) if tree.parent[c] == v] for v in range(N)]
+
+    def continuation(emitted, n):
+        """`emitted` followed by what plain greedy decoding (root-only steps, launched directly)
+        appends; recomputed when a near-tie made the tree step commit another token."""
+        t = list(emitted[:-1]) + ref.prefill([prompt + list(emitted[:-1])])
+        while len(t) < len(emitted) + n:
+            t += ref.step([-1], [0], [0])[0]
+        return t
+
+    def run(eng, steps):
+        emitted = eng.prefill([prompt])
+        out = [list(emitted)]
+        g = continuation(emitted, 8)
+        for i in range(steps):
+            if g[:len(emitted)] != emitted or len(g) < len(emitted) + cfg.k + 1:
+                g = continuation(emitted, 8)
+            if eng.drafts()[1][0] and i % 2 == 0:      # plant i/2 mod (k+1) true tokens along the last children
+                cand = [(t + 3) % cfg.vocab for t in synth.prompt_tokens(i, N, cfg.vocab, stream=3).tolist()]
+                v = 0
+                for lvl in range((i // 2) % (cfg.k + 1)):
+                    v = kids[v][-1]
+                    cand[v] = g[len(emitted) + lvl]
+                toks = eng.step_with_candidates(*args, [cand])[0]
+            else:
+                toks = eng.step(*args)[0]               # own drafts, or the root alone when there are none
+            emitted += toks
+            d, valid = eng.drafts()
+            out.append((toks, eng.last_path()[0], d.tolist(), valid, eng.last_logits().copy()))
+        return out
+
+    a = run(eng_g, 24)
+    b = run(eng_e, 24)
+    assert eng_g.stat("graph_launches") >= 20 and eng_e.stat("graph_launches") == 0
+    assert eng_g.stat("graph_captures") <= 6
+    assert max(len(x[0]) for x in a[1:]) >= 2          # candidates were accepted
+    assert any(x[4].shape[1] == 1 + cfg.k for x in a[1:])   # ... and root-only steps followed
+    a2 = run(eng_g, 24)
+    for x, y in ((a, b), (a, a2)):
+        assert x[0] == y[0]
+        for i, (p, q) in enumerate(zip(x[1:], y[1:])):
+            assert p[0] == q[0] and p[1] == q[1] and p[2] == q[2] and p[3] == q[3], f"step {i}"
+            assert np.array_equal(p[4], q[4]), f"step {i}: logits differ"
+    progress(f"graph replays {name}: {eng_g.stat('graph_launches')} launches, {eng_g.stat('graph_captures')} captures")
