@@ -34,10 +34,11 @@ def build(verbose: bool = True) -> str:
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError(f"link failed:\n{r.stderr}")
-    # standalone per-kernel benchmark (links the library; used for rocprofv3 counter runs)
-    tool = os.path.join(HERE, "bench_projection")
-    cmd = ["hipcc", *FLAGS, os.path.join(CSRC, "bench_projection.hip"), "-o", tool, f"-L{HERE}", "-lfirp",
-           "-Wl,-rpath,$ORIGIN"]
+    # standalone per-kernel benchmark beside bench.py (links the library; the rocprofv3 counter runs use it)
+    root = os.path.dirname(HERE)
+    tool = os.path.join(root, "bench_projection")
+    cmd = ["hipcc", *FLAGS, f"-I{CSRC}", os.path.join(root, "bench_projection.hip"), "-o", tool, f"-L{HERE}", "-lfirp",
+           f"-Wl,-rpath,$ORIGIN/{os.path.basename(HERE)}"]
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError(f"building bench_projection failed:\n{r.stderr}")
