@@ -163,8 +163,9 @@ def main() -> int:
                          "continuation so that 0, 1, .. k candidates are accepted in rotation, as trained maps would "
                          "have it: with the root as the only anchor every step that accepts a candidate is followed "
                          "by a root-only step (no drafts)")
-    ap.add_argument("--no-graph", action="store_true", help="launch every kernel of a step directly instead of "
-                                                            "replaying the step as a captured HIP graph")
+    ap.add_argument("--graph", type=int, default=2, choices=[0, 1, 2],
+                    help="replay the step as a captured HIP graph: 0 never, 1 whenever possible, 2 (default) the "
+                         "library's own rule (only models whose step is short)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a plain 1 GiB device copy three times (reference for scaling the "
@@ -206,8 +207,7 @@ def main() -> int:
     total_steps = args.warmup + args.steps + 16 + (2 * (args.warmup + args.steps) if args.accept_pattern else 0)
     eng = binding.engine_for_config(cfg, weights, max_ctx=prompt_len + (cfg.k + 1) * (total_steps + 2) + 8,
                       max_batch=args.batch, max_nodes=tree.n_nodes, max_rows=max(128, t_hi), b_max=8)
-    if args.no_graph:
-        eng.set_option("graph", 0)
+    eng.set_option("graph", args.graph)
     prompts = [synth.prompt_tokens(cfg.seed, prompt_len, cfg.vocab, stream=b).tolist() for b in range(args.batch)]
     prompt = prompts[0]
     eng.prefill(prompts)

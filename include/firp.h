@@ -229,7 +229,10 @@ firp_status firp_debug_read_cache(firp_ctx *ctx, int32_t seq, int32_t layer, flo
 
 /* Behaviour switches for tests and measurements.  name = "gemm" value 0 (plain tiled kernel)
  * or 1 (MFMA weight-streaming kernel, bf16 models only; the default for them); "time_gemm" 0/1
- * (see firp_get_gemm_timing); "keep_logits" 0/1 (default 0: see firp_debug_last_logits).  Returns FIRP_EINVAL for an unknown name or value. */
+ * (see firp_get_gemm_timing); "keep_logits" 0/1 (default 0: see firp_debug_last_logits);
+ * "graph" 0 / 1 / 2: replay the decoding step of a resident topology as a captured HIP graph
+ * never / whenever the stream and the kernels allow it / only for models whose step is short
+ * enough for the replay to pay (the default; the stream must not be the legacy default stream).  Returns FIRP_EINVAL for an unknown name or value. */
 firp_status firp_set_option(firp_ctx *ctx, const char *name, int32_t value);
 
 /* With option "time_gemm" = 1 every launch of the MFMA projection kernel inside firp_step is

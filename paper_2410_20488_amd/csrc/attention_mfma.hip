@@ -67,7 +67,8 @@ __device__ __forceinline__ int global_row(const SeqRows& sr, int b, int local) {
 // blockIdx = (sequence * tiles + tile, group of 128/dh heads); 2*dh threads per head: thread
 // (r16, c), c fastest, owns dims [4c, 4c+4) and their rotation partners [4c + dh/2, ...), so a
 // wave reads whole rows of the partial sums in 16-byte pieces.
-template <int DH>
+// SMAX: upper bound of the split factor of the instance (its loads are all in flight at once).
+template <int DH, int SMAX>
 __global__ __launch_bounds__(256) void k_rope_kv_tiles(Partial qkv, RowScale rs, int n_q_heads, SeqRows sr,
                                                        int n_local, int n_tiles, int seq0,
                                                        const int* __restrict__ p0v, const float2* __restrict__ tab,
@@ -87,9 +88,9 @@ __global__ __launch_bounds__(256) void k_rope_kv_tiles(Partial qkv, RowScale rs,
     const int row = global_row(sr, b, local);
     const size_t col = (size_t)row * qkv.ld + (size_t)h * DH + 4 * c;
     // all splits' loads in flight at once (split-K never exceeds 16)
-    float4 va[16], vb[16];
+    float4 va[SMAX], vb[SMAX];
 #pragma unroll
-    for (int u = 0; u < 16; ++u)
+    for (int u = 0; u < SMAX; ++u)
       if (u < qkv.S) {
         const float* pp = qkv.p + (size_t)u * qkv.stride + col;
         va[u] = *(const float4*)pp;
@@ -97,7 +98,7 @@ __global__ __launch_bounds__(256) void k_rope_kv_tiles(Partial qkv, RowScale rs,
       }
     float x1[4] = {0.f, 0.f, 0.f, 0.f}, x2[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-    for (int u = 0; u < 16; ++u)
+    for (int u = 0; u < SMAX; ++u)
       if (u < qkv.S) {
         x1[0] += va[u].x; x1[1] += va[u].y; x1[2] += va[u].z; x1[3] += va[u].w;
         x2[0] += vb[u].x; x2[1] += vb[u].y; x2[2] += vb[u].z; x2[3] += vb[u].w;
@@ -180,12 +181,15 @@ void launch_rope_kv_tiles(const Partial& qkv, const RowScale& rs, int n_q_heads,
   SeqRows sr{n_real_per_seq, std::max(1, n_anchor_per_seq), B * n_real_per_seq, B * n_anchor_per_seq};
   const int dh = kv.head_dim, heads = n_q_heads + 2 * kv.n_kv_heads, hpb = 128 / dh;
   dim3 g(B * n_tiles, (heads + hpb - 1) / hpb), blk(256);
-  if (dh == 128)
-    hipLaunchKernelGGL(k_rope_kv_tiles<128>, g, blk, 0, s, qkv, rs, n_q_heads, sr, n_local, n_tiles, seq0, p0, tab, q_frag, kv);
-  else if (dh == 64)
-    hipLaunchKernelGGL(k_rope_kv_tiles<64>, g, blk, 0, s, qkv, rs, n_q_heads, sr, n_local, n_tiles, seq0, p0, tab, q_frag, kv);
-  else
-    hipLaunchKernelGGL(k_rope_kv_tiles<32>, g, blk, 0, s, qkv, rs, n_q_heads, sr, n_local, n_tiles, seq0, p0, tab, q_frag, kv);
+  auto go = [&](auto kern) { hipLaunchKernelGGL(kern, g, blk, 0, s, qkv, rs, n_q_heads, sr, n_local, n_tiles, seq0, p0, tab, q_frag, kv); };
+  const int sm = qkv.S <= 4 ? 4 : qkv.S <= 8 ? 8 : 16;
+  if (dh == 128) {
+    if (sm == 4) go(k_rope_kv_tiles<128, 4>); else if (sm == 8) go(k_rope_kv_tiles<128, 8>); else go(k_rope_kv_tiles<128, 16>);
+  } else if (dh == 64) {
+    if (sm == 4) go(k_rope_kv_tiles<64, 4>); else if (sm == 8) go(k_rope_kv_tiles<64, 8>); else go(k_rope_kv_tiles<64, 16>);
+  } else {
+    if (sm == 4) go(k_rope_kv_tiles<32, 4>); else if (sm == 8) go(k_rope_kv_tiles<32, 8>); else go(k_rope_kv_tiles<32, 16>);
+  }
 }
 
 template <int DH>

@@ -55,7 +55,7 @@ void launch_embed(const void* embed, int dtype, const int* tok, int rows, int d,
 // of the row in pieces (the 1/rms factor is applied by whoever consumes the projection of act,
 // see RowScale).  blockIdx = (row, piece): a piece is 1024 columns, one float4 per thread, all
 // loads of a thread independent 128-bit loads.
-template <typename GT, bool SPLIT, bool NORM>
+template <typename GT, bool SPLIT, bool NORM, int SMAX>
 __global__ __launch_bounds__(256) void k_add_rmsnorm(float* x, Partial part, int d, const GT* __restrict__ gain,
                                                      Act out, float* __restrict__ ss_out) {
   __shared__ float red[4];
@@ -67,12 +67,12 @@ __global__ __launch_bounds__(256) void k_add_rmsnorm(float* x, Partial part, int
     float4 a = xr[i];
     if (part.p) {
       const float* pp = part.p + (size_t)r * part.ld + (size_t)i * 4;
-      float4 q[16];
+      float4 q[SMAX];
 #pragma unroll
-      for (int sp = 0; sp < 16; ++sp)
+      for (int sp = 0; sp < SMAX; ++sp)
         if (sp < part.S) q[sp] = *(const float4*)(pp + (size_t)sp * part.stride);
 #pragma unroll
-      for (int sp = 0; sp < 16; ++sp)
+      for (int sp = 0; sp < SMAX; ++sp)
         if (sp < part.S) {
           a.x += q[sp].x;
           a.y += q[sp].y;
@@ -98,19 +98,24 @@ int norm_pieces(int d) { return (d / 4 + 255) / 256; }
 void launch_add_rmsnorm(float* x, const Partial& part, int rows, int d, const void* gain, int dtype, const Act& out,
                         bool split, float* ss_out, hipStream_t s) {
   dim3 g(rows, norm_pieces(d)), b(256);
-  if (dtype == DT_BF16) {
-    if (split)
-      hipLaunchKernelGGL((k_add_rmsnorm<bf16, true, true>), g, b, 0, s, x, part, d, (const bf16*)gain, out, ss_out);
+  const int S = part.p ? part.S : 0;
+  if (dtype == DT_BF16 && split) {
+    if (S <= 4)
+      hipLaunchKernelGGL((k_add_rmsnorm<bf16, true, true, 4>), g, b, 0, s, x, part, d, (const bf16*)gain, out, ss_out);
+    else if (S <= 8)
+      hipLaunchKernelGGL((k_add_rmsnorm<bf16, true, true, 8>), g, b, 0, s, x, part, d, (const bf16*)gain, out, ss_out);
     else
-      hipLaunchKernelGGL((k_add_rmsnorm<bf16, false, true>), g, b, 0, s, x, part, d, (const bf16*)gain, out, ss_out);
+      hipLaunchKernelGGL((k_add_rmsnorm<bf16, true, true, 16>), g, b, 0, s, x, part, d, (const bf16*)gain, out, ss_out);
+  } else if (dtype == DT_BF16) {
+    hipLaunchKernelGGL((k_add_rmsnorm<bf16, false, true, 16>), g, b, 0, s, x, part, d, (const bf16*)gain, out, ss_out);
   } else {
-    hipLaunchKernelGGL((k_add_rmsnorm<float, false, true>), g, b, 0, s, x, part, d, (const float*)gain, out, ss_out);
+    hipLaunchKernelGGL((k_add_rmsnorm<float, false, true, 16>), g, b, 0, s, x, part, d, (const float*)gain, out, ss_out);
   }
 }
 
 void launch_add_partial(float* x, const Partial& part, int rows, int d, hipStream_t s) {
   Act none{};
-  hipLaunchKernelGGL((k_add_rmsnorm<float, false, false>), dim3(rows, norm_pieces(d)), dim3(256), 0, s, x, part, d,
+  hipLaunchKernelGGL((k_add_rmsnorm<float, false, false, 16>), dim3(rows, norm_pieces(d)), dim3(256), 0, s, x, part, d,
                      (const float*)nullptr, none, (float*)nullptr);
 }
 

@@ -141,6 +141,7 @@ def test_captured_step_replays_match_direct_launches(name, dev, progress):
     eng_g = make_engine(cfg, w, max_ctx=800, max_nodes=N, max_rows=64)
     eng_e = make_engine(cfg, w, max_ctx=800, max_nodes=N, max_rows=64)
     eng_e.set_option("graph", 0)
+    eng_g.set_option("graph", 1)
     ref = make_engine(cfg, w, max_ctx=800, max_nodes=1, max_rows=8)
     ref.set_option("graph", 0)
     kids = [[c for c in range(N) if tree.parent[c] == v] for v in range(N)]
