@@ -15,7 +15,9 @@
  *  - All argument and capacity checks run on the host before anything is enqueued; a failed
  *    call leaves the context unchanged.
  *  - The library never allocates or frees device memory and creates no streams: weights, the
- *    workspace and the stream are the caller's.  Pointers marked DEVICE must be device
+ *    workspace and the stream are the caller's.  (Two exceptions, both stated where they
+ *    apply: firp_debug_gemm_static owns one fixed buffer per GPU, and a step replayed as a
+ *    captured graph - option "graph" - holds what the HIP runtime allocates for the graph.)  Pointers marked DEVICE must be device
  *    addresses valid on the current HIP device; pointers marked HOST are ordinary host memory
  *    read or written during the call only.
  *  - Weights are `[out, in]` row-major in `dtype`, borrowed: they must outlive the context

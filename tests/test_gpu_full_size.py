@@ -77,11 +77,11 @@ def test_7b_full_depth_8k_context(progress):
 def test_34b_widths_batch_of_four_2k_prompts(progress):
     """The 34B-shaped workload's own batch and prompt sizes: four sequences with prompts of about
     2048 tokens (unequal: 2048, 2011, 1987, 2040), 4 x 67 = 268 rows in every projection, grouped
-    key/value heads, at the depth the oracle finishes in about a minute: 6 of the 48 layers, the
-    maps at layer 3.  Three steps in lockstep with one oracle per sequence."""
+    key/value heads, at the depth the four oracles finish in about a minute: 4 of the 48 layers, the
+    maps at layer 2.  Three steps in lockstep with one oracle per sequence."""
     from tests.gpu_common import run_lockstep_batch
     dev = torch.device("cuda:0")
-    cfg = synth.scaled_config(synth.CONFIGS["34b"], 6, 3)
+    cfg = synth.scaled_config(synth.CONFIGS["34b"], 4, 2)
     progress("34b 2k: generating weights")
     w = synth.make_weights(cfg, dev)
     tree = synth.workload_tree("34b")
