@@ -570,7 +570,7 @@ firp_status upload_tree(firp_ctx* c, int B, const std::vector<int>& parent, cons
     std::vector<int> fill(cstart.begin(), cstart.end() - 1);
     for (int v = 1; v < N; ++v) clist[fill[parent[v]]++] = v;  // ascending node id per parent
   }
-  int P = k * n_anchor, T = N + P, R = B * T;
+  const int P = k * n_anchor;
   // one host image of the slot, one copy
   const TopoLayout& t = c->tl_off;
   std::vector<char> img(t.bytes, 0);
@@ -604,7 +604,6 @@ firp_status upload_tree(firp_ctx* c, int B, const std::vector<int>& parent, cons
       }
     }
   }
-  (void)R;
   std::copy(parent.begin(), parent.end(), (int*)(img.data() + t.parent));
   std::copy(depth.begin(), depth.end(), (int*)(img.data() + t.level));
   std::copy(rank.begin(), rank.end(), (int*)(img.data() + t.rank));

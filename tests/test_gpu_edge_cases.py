@@ -166,3 +166,31 @@ def test_more_topologies_than_the_library_keeps(progress):
             assert eng.drafts()[0][0].tolist() == r.drafts
     # 1 (the prefill's root-only step) + 6 first uses + the re-uploads of evicted ones
     assert eng.stat("topo_uploads") >= 7
+
+
+@pytest.mark.parametrize("name", ["tiny", "tiny_bf16"])
+def test_steps_without_kept_logits(name):
+    """By default a step leaves no logits in memory (it needs the greedy token of every node and
+    the top-b ids of the pseudo rows only): tokens, paths, drafts and cache lengths must be those
+    of an engine that keeps them, and the logits read-out must refuse."""
+    from paper_2410_20488_amd.binding import FirpError
+    cfg = synth.CONFIGS[name]
+    w = synth.make_weights(cfg, DEV, with_bias=True)
+    tree = synth.full_tree((3, 2), "all")
+    args = (list(tree.parent), list(tree.rank), list(tree.anchor))
+    prompt = synth.prompt_tokens(cfg.seed + 2, 37, cfg.vocab).tolist()
+    eng_a = make_engine(cfg, w, max_ctx=128, max_nodes=tree.n_nodes, max_rows=64)
+    eng_b = make_engine(cfg, w, max_ctx=128, max_nodes=tree.n_nodes, max_rows=64, keep_logits=False)
+    assert eng_a.prefill([prompt]) == eng_b.prefill([prompt])
+    for step in range(10):
+        if step % 3 == 1:
+            cand = [synth.prompt_tokens(step, tree.n_nodes, cfg.vocab, stream=4).tolist()]
+            ta, tb = eng_a.step_with_candidates(*args, cand), eng_b.step_with_candidates(*args, cand)
+        else:
+            ta, tb = eng_a.step(*args), eng_b.step(*args)
+        assert ta == tb and eng_a.last_path() == eng_b.last_path() and eng_a.ctx_len() == eng_b.ctx_len()
+        da, db = eng_a.drafts(), eng_b.drafts()
+        assert da[1] == db[1] and np.array_equal(da[0], db[0])
+        with pytest.raises(FirpError) as e:
+            eng_b.last_logits()
+        assert e.value.code == -2
