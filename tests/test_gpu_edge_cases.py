@@ -194,3 +194,16 @@ def test_steps_without_kept_logits(name):
         with pytest.raises(FirpError) as e:
             eng_b.last_logits()
         assert e.value.code == -2
+
+
+def test_two_long_sequences_replayed_as_graphs(progress):
+    """Two sequences with contexts long enough (and different enough) for the captured-graph
+    path: the attention kernel takes each sequence's chunk length from its own committed length
+    on the device.  Lockstep with one oracle per sequence; most steps must have been replays."""
+    cfg = synth.CONFIGS["tiny_bf16"]
+    w = synth.make_weights(cfg, DEV, with_bias=True)
+    tree = synth.full_tree((3, 2), "root")
+    rep, eng, orcs = run_lockstep_batch(cfg, w, tree, prompt_lens=[640, 531], n_steps=9, tol=2e-2, max_rows=32,
+                                        progress=progress)
+    assert rep.steps == 9 and sum(rep.accepted_hist[2:]) > 0
+    assert eng.stat("graph_launches") >= 7, eng.stat("graph_launches")
