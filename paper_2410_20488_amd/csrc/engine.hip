@@ -270,6 +270,7 @@ size_t carve(firp_ctx* c, char* base) {
   c->st.drafts_valid = cv.take<int>(B);
   c->st.tok = cv.take<int>(R);
   c->st.amax = cv.take<int>(R);
+  c->st.top = cv.take<int>((size_t)R * d.b_max);
   c->st.result = cv.take<int>((size_t)B * FIRP_RESULT_STRIDE);
   c->st.k = c->k;
   c->st.b_max = d.b_max;
@@ -489,8 +490,8 @@ firp_status forward(firp_ctx* c, int B, int N, int n_anchor, bool head, int max_
       // the logits themselves are written only on request (tests, the training forward): the step
       // needs the greedy token of every node and the top-b ids of every pseudo row, nothing else
       const bool want_logits = c->keep_logits || c->force_logits;
-      launch_argmax_part(lg, rs, want_logits ? c->logits : nullptr, real_rows, rows, d.vocab, d.b_max,
-                         c->argmax_scratch, s);
+      launch_argmax_topb(lg, rs, want_logits ? c->logits : nullptr, real_rows, rows, d.vocab, d.b_max, c->st.amax,
+                         c->st.top, c->argmax_scratch, s);
       c->last_has_logits = want_logits;
       break;
     }
@@ -733,7 +734,7 @@ firp_status run_step(firp_ctx* c, const firp_tree* tree, const int32_t* node_tok
     }
     firp_status fs = forward(c, B, N, n_anchor, true, ctx_max, 0, 0, c->k);
     if (fs != FIRP_OK) return fs;
-    launch_merge_verify_select(c->argmax_scratch, c->st, tree_tab(c, N, P), B, c->d.vocab, s);
+    launch_verify_select(c->st, tree_tab(c, N, P), B, s);
     launch_kv_compact(kv_view(c, 0), c->kv_layer_stride, c->d.n_layers, B, c->st, c->dtype, s);
     return FIRP_OK;
   };

@@ -39,6 +39,7 @@ struct SeqState {
   int* drafts_valid; // [B]
   int* tok;          // [B][N] token of every node of the running step
   int* amax;         // [B*N] greedy token per real row
+  int* top;          // [B*P][b_max] top-b ids per pseudo row
   int* result;       // [B][RESULT_STRIDE]: n_emitted, drafts_valid, p0 before, tokens[k_cap+1], path[k_cap+1]
   int k, b_max, k_cap;
 };
@@ -75,20 +76,14 @@ struct PseudoBias {
 };
 void launch_scatter_pseudo(const Partial& y, int n_anchor_rows, int d, int k, int i0, int k_in_y,
                            const PseudoBias& bias, int dtype, float* x, int first_pseudo_row, hipStream_t s);
-// lm-head consumer, first level: per vocabulary segment the best entries of every row (one for a
-// real row, b_max for a pseudo row) into `scratch` (>= argmax_scratch_bytes); with `logits_out`
-// it also leaves the summed, scaled logits.
+// greedy token of every real row and top-b of every pseudo row; also leaves summed logits.
+// (two launches: per vocabulary segment, then a merge; `scratch` >= argmax_scratch_bytes)
 size_t argmax_scratch_bytes(int rows, int b_max);
-void launch_argmax_part(const Partial& logits, const RowScale& rs, float* logits_out, int real_rows, int rows,
-                        int vocab, int b_max, void* scratch, hipStream_t s);
-// second level fused with the greedy verification and the draft selection: the greedy token of
-// every node, the longest accepted path, and the top-b ids of the pseudo rows of the path's last
-// node as the next drafts (only those k rows are merged)
-#define FIRP_MAX_ROWS_PER_SEQ 256
-void launch_merge_verify_select(const void* scratch, const SeqState& st, const TreeTab& tt, int B, int vocab,
-                                hipStream_t s);
+void launch_argmax_topb(const Partial& logits, const RowScale& rs, float* logits_out, int real_rows, int rows,
+                        int vocab, int b_max, int* amax, int* top, void* scratch, hipStream_t s);
 // Training stage, Eq. 4: kl[q] = KL(softmax(logits[n+q]) , softmax(logits[q+step])), q < n - step
 void launch_kl_rows(const float* logits, int vocab, int n, int step, float* kl, hipStream_t s);
+void launch_verify_select(const SeqState& st, const TreeTab& tt, int B, hipStream_t s);
 // move the accepted path's K/V to the front of the step's slots; advances nothing.
 void launch_kv_compact(const KvView& kv_layer0, size_t layer_stride, int n_layers, int B,
                        const SeqState& st, int dtype, hipStream_t s);

@@ -290,8 +290,8 @@ __device__ __forceinline__ bool better(float v, int id, const Best& o) {
 // Two levels.  k_argmax_part: blockIdx = (row, vocabulary segment); one pass over the segment,
 // every thread keeps the best BM entries of its strided share in registers (sorted insertion),
 // then `want` rounds of a block-wide arg-best over the threads' current heads leave the
-// segment's best entries, in order, in cand[row][segment][BM].  k_merge_verify_select picks a
-// row's top entries out of the segments' candidates the same way, for the rows it needs.
+// segment's best entries, in order, in cand[row][segment][BM].  k_argmax_merge: one block per
+// row picks the row's top entries out of the segments' candidates the same way.
 #define FIRP_ARGMAX_SEGS 8
 template <int BM>
 __global__ __launch_bounds__(256) void k_argmax_part(Partial lg, RowScale rs, float* logits_out, int real_rows,
@@ -349,11 +349,12 @@ __global__ __launch_bounds__(256) void k_argmax_part(Partial lg, RowScale rs, fl
   }
 }
 
-// One wave merges the segments' candidates of row r: the row's `want` best entries, in order,
-// go to out[0..want) (every lane returns; lane 0 writes).  lane = (segment, slot) for up to 8
-// segments x 8 slots; with BM = 16 a lane holds two slots.
 template <int BM>
-__device__ __forceinline__ void merge_row(const Best* __restrict__ cand, int r, int want, int vocab, int lane, int* out) {
+__global__ __launch_bounds__(64) void k_argmax_merge(const Best* __restrict__ cand, int real_rows, int vocab,
+                                                     int b_max, int* amax, int* top) {
+  const int r = blockIdx.x, lane = threadIdx.x;
+  const int want = (r < real_rows) ? 1 : b_max;
+  // lane = (segment, slot) for up to 8 segments x 8 slots; with BM = 16 a lane holds two slots
   constexpr int PER = (FIRP_ARGMAX_SEGS * BM + 63) / 64;
   Best mine[PER];
 #pragma unroll
@@ -377,67 +378,12 @@ __device__ __forceinline__ void merge_row(const Best* __restrict__ cand, int r, 
       mine[PER - 1] = Best{-__builtin_inff(), 0x7fffffff};
     }
     if (win >= vocab) win = 0;  // only when every remaining logit is NaN
-    if (lane == 0) out[p] = win;
-  }
-}
-
-// Merge + greedy verification + draft selection (Inference stage), one workgroup of four waves
-// per sequence:
-//  1. the greedy token of every node of the sequence (merge of the segments' candidates);
-//  2. from the root, emit the greedy token of the current node and move to the child that
-//     carries it (lowest node id if several do); stop when none does;
-//  3. the next drafts are the top-b ids of the pseudo rows of the node that ends the path - only
-//     these k rows are merged, whatever the number of anchors.
-template <int BM>
-__global__ __launch_bounds__(256) void k_merge_verify_select(const Best* __restrict__ cand, SeqState st, TreeTab tt,
-                                                             int vocab) {
-  __shared__ int s_amax[FIRP_MAX_ROWS_PER_SEQ];
-  __shared__ int s_cur;
-  const int b = blockIdx.x, B = gridDim.x, N = tt.n_nodes;
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  for (int v = wave; v < N; v += 4) merge_row<BM>(cand, b * N + v, 1, vocab, lane, &s_amax[v]);
-  __syncthreads();
-  for (int v = threadIdx.x; v < N; v += blockDim.x) st.amax[b * N + v] = s_amax[v];
-  int* res = st.result + b * FIRP_RESULT_STRIDE;
-  if (threadIdx.x == 0) {
-    const int* tok = st.tok + b * N;
-    int cur = 0, n = 0;
-    int* out_tok = res + 3;
-    int* out_path = res + 3 + (st.k_cap + 1);
-    while (true) {
-      int t = s_amax[cur];
-      out_tok[n] = t;
-      out_path[n] = cur;
-      ++n;
-      int nxt = -1;
-      for (int e = tt.child_start[cur]; e < tt.child_start[cur + 1]; ++e) {
-        int c = tt.child_list[e];
-        if (tok[c] == t) {
-          nxt = c;
-          break;
-        }
-      }
-      if (nxt < 0 || n > st.k_cap) break;  // n <= k_cap + 1 by the depth check on the host
-      cur = nxt;
+    if (lane == 0) {
+      if (r < real_rows)
+        amax[r] = win;
+      else
+        top[(size_t)(r - real_rows) * b_max + p] = win;
     }
-    int pb = tt.pseudo_base[cur];
-    res[0] = n;
-    res[1] = (pb >= 0 && st.k > 0) ? 1 : 0;
-    res[2] = st.p0[b];  // cache length before this step's commit
-    st.p0[b] += n;
-    st.root_tok[b] = out_tok[n - 1];
-    st.drafts_valid[b] = res[1];
-    s_cur = cur;
-  }
-  __syncthreads();
-  const int pb = tt.pseudo_base[s_cur];
-  if (pb >= 0 && st.k > 0) {
-    // pseudo rows are ordered step by step: step i of anchor a of sequence b is row
-    // B*N + i * (B * A) + b * A + a
-    const int A = tt.n_anchor, a = pb - N;
-    for (int i = wave; i < st.k; i += 4)
-      merge_row<BM>(cand, B * N + i * B * A + b * A + a, st.b_max, vocab, lane,
-                    st.drafts + ((size_t)b * st.k + i) * st.b_max);
   }
 }
 
@@ -445,24 +391,17 @@ size_t argmax_scratch_bytes(int rows, int b_max) {
   return (size_t)rows * FIRP_ARGMAX_SEGS * (b_max <= 8 ? 8 : 16) * sizeof(Best);
 }
 
-// per vocabulary segment, the best entries of every row (and, on request, the logits themselves)
-void launch_argmax_part(const Partial& logits, const RowScale& rs, float* logits_out, int real_rows, int rows,
-                        int vocab, int b_max, void* scratch, hipStream_t s) {
+void launch_argmax_topb(const Partial& logits, const RowScale& rs, float* logits_out, int real_rows, int rows,
+                        int vocab, int b_max, int* amax, int* top, void* scratch, hipStream_t s) {
   Best* cand = (Best*)scratch;
   dim3 g(rows, FIRP_ARGMAX_SEGS);
-  if (b_max <= 8)
+  if (b_max <= 8) {
     hipLaunchKernelGGL(k_argmax_part<8>, g, dim3(256), 0, s, logits, rs, logits_out, real_rows, vocab, b_max, cand);
-  else
+    hipLaunchKernelGGL(k_argmax_merge<8>, dim3(rows), dim3(64), 0, s, cand, real_rows, vocab, b_max, amax, top);
+  } else {
     hipLaunchKernelGGL(k_argmax_part<16>, g, dim3(256), 0, s, logits, rs, logits_out, real_rows, vocab, b_max, cand);
-}
-
-void launch_merge_verify_select(const void* scratch, const SeqState& st, const TreeTab& tt, int B, int vocab,
-                                hipStream_t s) {
-  const Best* cand = (const Best*)scratch;
-  if (st.b_max <= 8)
-    hipLaunchKernelGGL(k_merge_verify_select<8>, dim3(B), dim3(256), 0, s, cand, st, tt, vocab);
-  else
-    hipLaunchKernelGGL(k_merge_verify_select<16>, dim3(B), dim3(256), 0, s, cand, st, tt, vocab);
+    hipLaunchKernelGGL(k_argmax_merge<16>, dim3(rows), dim3(64), 0, s, cand, real_rows, vocab, b_max, amax, top);
+  }
 }
 
 // ------------------------------------------------------------------------------------------
@@ -509,6 +448,63 @@ __global__ __launch_bounds__(256) void k_kl_rows(const float* __restrict__ logit
 
 void launch_kl_rows(const float* logits, int vocab, int n, int step, float* kl, hipStream_t s) {
   hipLaunchKernelGGL(k_kl_rows, dim3(n - step), dim3(256), 0, s, logits, vocab, n, step, kl);
+}
+
+// ------------------------------------------------------------------------------------------
+// Greedy verification (Inference stage): from the root, emit the greedy token of the current
+// node and move to the child that carries it (lowest node id if several do); stop when none
+// does.  Then read the next drafts off the pseudo rows of the node that ends the path.
+__global__ void k_verify_select(SeqState st, TreeTab tt) {
+  int b = blockIdx.x;
+  int N = tt.n_nodes;
+  int* res = st.result + b * FIRP_RESULT_STRIDE;
+  __shared__ int s_cur;
+  if (threadIdx.x == 0) {
+    const int* tok = st.tok + b * N;
+    const int* amax = st.amax + b * N;
+    int cur = 0, n = 0;
+    int* out_tok = res + 3;
+    int* out_path = res + 3 + (st.k_cap + 1);
+    while (true) {
+      int t = amax[cur];
+      out_tok[n] = t;
+      out_path[n] = cur;
+      ++n;
+      int nxt = -1;
+      for (int e = tt.child_start[cur]; e < tt.child_start[cur + 1]; ++e) {
+        int c = tt.child_list[e];
+        if (tok[c] == t) {
+          nxt = c;
+          break;
+        }
+      }
+      if (nxt < 0 || n > st.k_cap) break;  // n <= k_cap + 1 by the depth check on the host
+      cur = nxt;
+    }
+    int pb = tt.pseudo_base[cur];
+    res[0] = n;
+    res[1] = (pb >= 0 && st.k > 0) ? 1 : 0;
+    res[2] = st.p0[b];  // cache length before this step's commit
+    st.p0[b] += n;
+    st.root_tok[b] = out_tok[n - 1];
+    st.drafts_valid[b] = res[1];
+    s_cur = cur;
+  }
+  __syncthreads();
+  int pb = tt.pseudo_base[s_cur];
+  if (pb >= 0 && st.k > 0) {
+    // pseudo rows are ordered step by step: step i of anchor a of sequence b is pseudo row
+    // i * (B * A) + b * A + a
+    const int B = gridDim.x, A = tt.n_anchor, a = pb - N;
+    for (int e = threadIdx.x; e < st.k * st.b_max; e += blockDim.x) {
+      const int i = e / st.b_max, j = e - i * st.b_max;
+      st.drafts[(size_t)b * st.k * st.b_max + e] = st.top[((size_t)i * B * A + (size_t)b * A + a) * st.b_max + j];
+    }
+  }
+}
+
+void launch_verify_select(const SeqState& st, const TreeTab& tt, int B, hipStream_t s) {
+  hipLaunchKernelGGL(k_verify_select, dim3(B), dim3(64), 0, s, st, tt);
 }
 
 // ------------------------------------------------------------------------------------------
