@@ -207,3 +207,29 @@ def test_two_long_sequences_replayed_as_graphs(progress):
                                         progress=progress)
     assert rep.steps == 9 and sum(rep.accepted_hist[2:]) > 0
     assert eng.stat("graph_launches") >= 7, eng.stat("graph_launches")
+
+
+def test_default_stream_falls_back_to_direct_launches(progress):
+    """The legacy default stream cannot be captured: with graph replay asked for, a context on
+    that stream must notice, launch its kernels directly and give the same results as a context
+    on a stream of its own."""
+    from paper_2410_20488_amd import binding
+    cfg = synth.CONFIGS["tiny_bf16"]
+    w = synth.make_weights(cfg, DEV, with_bias=True)
+    tree = synth.full_tree((3, 2), "root")
+    args = (list(tree.parent), list(tree.rank), list(tree.anchor))
+    prompt = synth.prompt_tokens(cfg.seed + 9, 600, cfg.vocab).tolist()
+    kw = dict(n_layers=cfg.n_layers, d_model=cfg.d_model, n_q_heads=cfg.n_q_heads, n_kv_heads=cfg.n_kv_heads,
+              head_dim=cfg.head_dim, d_ffn=cfg.d_ffn, vocab=cfg.vocab, rms_eps=cfg.rms_eps, rope_base=cfg.rope_base,
+              dtype=cfg.dtype, weights=w, firp_layer=cfg.firp_layer, k=cfg.k, max_ctx=700, max_nodes=tree.n_nodes,
+              max_rows=32)
+    eng_d = binding.Engine(stream=torch.cuda.default_stream(torch.device(DEV)), **kw)
+    eng_s = binding.Engine(**kw)
+    for e in (eng_d, eng_s):
+        e.set_option("graph", 1)
+        e.set_option("keep_logits", 1)
+    assert eng_d.prefill([prompt]) == eng_s.prefill([prompt])
+    for _ in range(6):
+        assert eng_d.step(*args) == eng_s.step(*args)
+        assert np.array_equal(eng_d.last_logits(), eng_s.last_logits())
+    assert eng_d.stat("graph_launches") == 0 and eng_s.stat("graph_launches") >= 5
