@@ -149,7 +149,9 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=128)
     ap.add_argument("--warmup", type=int, default=8)
-    ap.add_argument("--config", default="13b", choices=["13b", "7b", "34b", "tiny_bf16"])
+    ap.add_argument("--config", default="13b", choices=["13b", "7b", "34b", "tiny_bf16", "tiny"],
+                    help="13b (default): the headline workload; 7b, 34b: the other LLaMA shapes; tiny: the 4-layer fp32 "
+                         "correctness configuration (chain tree, prompt 64); tiny_bf16: the same widths in bf16")
     ap.add_argument("--batch", type=int, default=1, help="independent sequences decoded side by side")
     ap.add_argument("--prompt", type=int, default=0, help="prompt length (default: the configuration's)")
     ap.add_argument("--anchors", default="root", choices=["root", "all"])
@@ -198,7 +200,7 @@ def main() -> int:
         cfg = dataclasses.replace(cfg, firp_layers=tuple(int(t) for t in args.firp_layers.split(",")))
         assert len(cfg.firp_layers) == cfg.k
     tree = synth.workload_tree(args.tree or args.config, args.anchors)
-    prompt_len = args.prompt or {"13b": 1024, "7b": 512, "34b": 2048, "tiny_bf16": 64}[args.config]
+    prompt_len = args.prompt or {"13b": 1024, "7b": 512, "34b": 2048, "tiny_bf16": 64, "tiny": 64}[args.config]
     t_start = time.time()
     weights = synth.make_weights(cfg, dev)
     torch.cuda.synchronize()
@@ -260,8 +262,8 @@ def main() -> int:
         "metric": "firp_step latency (ms) and achieved HBM GB/s vs peak, 13B-shape bf16, k=3",
         "value": round(ms_per_step, 4), "unit": "ms/step", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": False,
-        "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": f"LLaMA-2-{args.config.upper()}-shaped decoder, bf16 random-init, k={cfg.k} maps at "
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16" if cfg.dtype == "bf16" else "f32", "data": "synthetic",
+        "config": {"workload": f"LLaMA-2-{args.config.upper()}-shaped decoder, {cfg.dtype} random-init, k={cfg.k} maps at "
                                f"layer {cfg.firp_layer if cfg.firp_layers is None else list(cfg.firp_layers)}, batch {args.batch}, prompt {prompt_len} uniform-random tokens, "
                                f"{tree.n_nodes}-node draft tree, anchors={args.anchors} (T_hi={t_hi}), "
                                f"ctx {ctx_first}->{ctx_last}"},
