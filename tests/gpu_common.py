@@ -36,6 +36,22 @@ def _tokens_from_drafts(tree: synth.Tree, depth, drafts, root):
     return [root] + [drafts[depth[v] - 1][tree.rank[v]] for v in range(1, tree.n_nodes)]
 
 
+def _report_long_layers(orc, progress, min_rows=1024, every=4):
+    """A long prompt keeps the oracle busy for minutes: let every few finished layers of such a
+    pass write a progress line (a quiet test must be distinguishable from a hung one)."""
+    if not progress:
+        return
+    inner = orc._layer
+
+    def layer(idx, x, *rest, **kw):
+        out = inner(idx, x, *rest, **kw)
+        if x.shape[0] >= min_rows and (idx + 1) % every == 0:
+            progress(f"oracle: layer {idx + 1} of {orc.L} done on {x.shape[0]} rows")
+        return out
+
+    orc._layer = layer
+
+
 def run_lockstep(cfg, weights_gpu, tree: synth.Tree, *, prompt_len: int, n_steps: int, tol: float,
                  gemm=None, b_max=8, with_injection=True, max_rows=128, progress=None, oracle_dtype=torch.float64,
                  max_ctx=None):
@@ -58,6 +74,7 @@ def run_lockstep(cfg, weights_gpu, tree: synth.Tree, *, prompt_len: int, n_steps
                       max_nodes=max(tree.n_nodes, 1), max_rows=max_rows, b_max=b_max, gemm=gemm)
     prompt = synth.prompt_tokens(cfg.seed, prompt_len, cfg.vocab).tolist()
     rep = LockstepReport(accepted_hist=[0] * (synth.FIRP_MAX_DEPTH + 2))
+    _report_long_layers(orc, progress)
     t_o = orc.prefill(prompt)
     t_g = eng.prefill([prompt])[0]
     if progress:
@@ -176,6 +193,8 @@ def run_lockstep_batch(cfg, weights_gpu, tree: synth.Tree, *, prompt_lens, n_ste
                       max_nodes=N, max_rows=max_rows or (N + k * n_anchor), b_max=b_max)
     prompts = [synth.prompt_tokens(cfg.seed + 31, n, cfg.vocab, stream=b).tolist() for b, n in enumerate(prompt_lens)]
     first = eng.prefill(prompts)
+    for o in orcs:
+        _report_long_layers(o, progress)
     assert first == [o.prefill(p) for o, p in zip(orcs, prompts)]
     emitted = [[t] for t in first]
     depth = [0] * N
