@@ -1,6 +1,9 @@
-// Plain LDS-tiled projection y[rows][n] = x[rows][K] . W[n][K]^T in fp32 arithmetic.
-// It serves fp32 models (the small correctness configuration) and is the selectable plain
-// path for bf16 models; the weight-streaming MFMA kernel is in gemm_mfma.hip.
+// Plain projections y[rows][n] = x[rows][K] . W[n][K]^T in fp32 arithmetic: an LDS-tiled kernel
+// for any row count and, for the up to 16 rows of a small decoding step, one wave per output
+// column.  They serve fp32 models (the small correctness configuration) and are the selectable
+// plain path for bf16 models; the weight-streaming MFMA kernel is in gemm_mfma.hip.
+#include <cstdint>
+
 #include "kernels.h"
 
 namespace firp {
@@ -51,8 +54,54 @@ __global__ __launch_bounds__(256) void k_gemm_simple(const float* __restrict__ x
   }
 }
 
+// Up to 16 rows: one wave per column of y.  A lane takes four consecutive k of its column's
+// weight row per round (the wave 256) and multiplies them with the same k of every row of x
+// (a few KB, cache hits); the rows' sums are then added across the wave in a fixed order.
+// K % 4 == 0, ldx % 4 == 0.
+__device__ __forceinline__ float4 load4(const float* p) { return *(const float4*)p; }
+__device__ __forceinline__ float4 load4(const bf16* p) {
+  const uint2 v = *(const uint2*)p;
+  return make_float4(__uint_as_float(v.x << 16), __uint_as_float(v.x & 0xffff0000u), __uint_as_float(v.y << 16),
+                     __uint_as_float(v.y & 0xffff0000u));
+}
+
+template <typename WT>
+__global__ __launch_bounds__(256) void k_gemm_skinny(const float* __restrict__ x, int ldx, const WT* __restrict__ w,
+                                                     float* __restrict__ y, int ldy, int rows, int n, int K) {
+  const int lane = threadIdx.x & 63, c = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (c >= n) return;
+  float acc[16];
+#pragma unroll
+  for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+  const WT* wr = w + (size_t)c * K;
+  for (int k = lane * 4; k < K; k += 256) {
+    const float4 a = load4(wr + k);
+#pragma unroll
+    for (int r = 0; r < 16; ++r)
+      if (r < rows) {
+        const float4 b = *(const float4*)(x + (size_t)r * ldx + k);
+        acc[r] += a.x * b.x + a.y * b.y + a.z * b.z + a.w * b.w;
+      }
+  }
+#pragma unroll
+  for (int r = 0; r < 16; ++r)
+    if (r < rows) {
+      const float t = wave_sum(acc[r]);
+      if (lane == 0) y[(size_t)r * ldy + c] = t;
+    }
+}
+
 void launch_gemm_simple(const float* x, int ldx, const void* w, int dtype, float* y, int ldy,
                         int rows, int n, int K, hipStream_t s) {
+  const bool aligned = ((uintptr_t)x & 15) == 0 && ((uintptr_t)w & 15) == 0;
+  if (rows <= 16 && K % 4 == 0 && ldx % 4 == 0 && aligned) {
+    dim3 gs((n + 3) / 4), bs(256);
+    if (dtype == DT_BF16)
+      hipLaunchKernelGGL(k_gemm_skinny<bf16>, gs, bs, 0, s, x, ldx, (const bf16*)w, y, ldy, rows, n, K);
+    else
+      hipLaunchKernelGGL(k_gemm_skinny<float>, gs, bs, 0, s, x, ldx, (const float*)w, y, ldy, rows, n, K);
+    return;
+  }
   dim3 g((n + 63) / 64, (rows + 63) / 64), b(256);
   if (dtype == DT_BF16)
     hipLaunchKernelGGL(k_gemm_simple<bf16>, g, b, 0, s, x, ldx, (const bf16*)w, y, ldy, rows, n, K);

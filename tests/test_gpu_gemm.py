@@ -39,7 +39,11 @@ def test_mfma_projection_matches_fp64_matmul(rows, n, K):
 
 
 @pytest.mark.parametrize("rows,n,K,dtype", [(7, 688, 256, torch.float32), (67, 1024, 688, torch.float32),
-                                            (130, 520, 352, torch.bfloat16), (3, 1000, 100, torch.float32)])
+                                            (130, 520, 352, torch.bfloat16), (3, 1000, 100, torch.float32),
+                                            # the one-wave-per-column kernel's range ends at 16 rows
+                                            (16, 1024, 256, torch.float32), (17, 256, 256, torch.float32),
+                                            (5, 520, 352, torch.bfloat16), (1, 4, 8, torch.float32),
+                                            (4, 1024, 2052, torch.float32), (11, 36, 1028, torch.bfloat16)])
 def test_plain_projection_matches_fp64_matmul(rows, n, K, dtype):
     x, w = _inputs(rows, n, K, dtype)
     y = binding.debug_gemm(x, w, kind=0).cpu().double()
